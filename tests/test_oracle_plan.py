@@ -1,0 +1,38 @@
+"""Pins for the attention plan oracle: exact cover, slice bound, maximality."""
+import numpy as np
+import pytest
+
+from oracle.plan import attention_plan
+
+
+@pytest.mark.parametrize("ctx,hkv,chunk,slice_bytes", [
+    ([1], 1, 16, 1), ([16, 17, 255, 256, 257], 8, 64, 64 * 512 * 3),
+    ([4096, 33, 512, 513, 8192], 2, 512, 1 << 20), ([100] * 7, 8, 128, 10 ** 9)])
+def test_plan_covers_every_token_once_and_bounds_slices(ctx, hkv, chunk, slice_bytes):
+    D, B = 128, 16
+    work, starts = attention_plan(ctx, hkv, D, B, chunk, slice_bytes)
+    seen = {}
+    for s, h, fb, nt in work.tolist():
+        assert 1 <= nt <= chunk and (fb * B) % chunk == 0
+        for t in range(fb * B, fb * B + nt):
+            assert (s, h, t) not in seen
+            seen[(s, h, t)] = 1
+    assert len(seen) == sum(ctx) * hkv
+    assert all((s, h, t) in seen for s, n in enumerate(ctx) for h in range(hkv) for t in (0, n - 1))
+    # launch order: sequence, then chunk, then head
+    keys = [(s, fb, h) for s, h, fb, _ in work.tolist()]
+    assert keys == sorted(keys)
+    assert starts[0] == 0 and starts[-1] == len(work) and np.all(np.diff(starts) >= 1)
+    nbytes = work[:, 3].astype(np.int64) * (2 * D * 2)
+    for a, b in zip(starts[:-1], starts[1:]):
+        tot = int(nbytes[a:b].sum())
+        assert tot <= slice_bytes or b - a == 1
+        if b < len(work):                       # maximal: the next item would not have fitted
+            assert tot + int(nbytes[b]) > slice_bytes
+
+
+def test_plan_rejects_bad_arguments():
+    with pytest.raises(ValueError):
+        attention_plan([5], 1, 64, 16, 24, 100)
+    with pytest.raises(ValueError):
+        attention_plan([5, 0], 1, 64, 16, 32, 100)

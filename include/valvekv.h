@@ -1,0 +1,246 @@
+/*
+ * valvekv — preemptible paged-KV decode attention and KV memory reclamation
+ * for one AMD MI355X (gfx950).  C ABI.
+ *
+ * The problem is the one stated for online-offline colocation in the Valve
+ * paper: an offline decode job fills the KV memory an online tenant leaves
+ * idle; when the online tenant needs compute or memory back, the offline job
+ * must stop within a sub-millisecond bound (Section 2.3, Challenge 1;
+ * Section 4), and KV memory must be handed back promptly, below layer
+ * granularity, without faults and without killing the offline job
+ * (Section 2.3, Challenge 2; Section 5, "Sub-layer memory reclamation").
+ *
+ * The paper answers with a driver-level channel switch and by discarding the
+ * reclaimed KV.  This library answers cooperatively:
+ *   - decode attention of a layer is issued as slices of bounded KV bytes, so a
+ *     yield lands at the next slice boundary and later resumes from a cursor;
+ *   - a reclaimed block range is emptied by copying its live blocks to free
+ *     blocks outside it and rewriting every block-table entry, so the offline
+ *     job keeps its KV and never reads handed-over memory.
+ *
+ * Conventions
+ *   - Every function returns an int status: VKV_OK (0), VKV_YIELDED (1) or a
+ *     negative VKV_E_* code.  vkv_last_error() gives a message for the calling
+ *     thread's last failure.  No exception crosses this boundary.
+ *   - "device" pointers are HIP device memory owned by the caller; "host"
+ *     pointers are ordinary host memory owned by the caller.  The library owns
+ *     only the opaque vkv_pool object (host memory, small pinned staging
+ *     buffers, HIP events).  It never allocates or frees device memory.
+ *   - Streams are hipStream_t passed as void* (NULL = the default stream).
+ *     Device work is enqueued on the given stream; unless stated otherwise a
+ *     call returns without waiting for it.
+ *   - One host thread at a time may call into a given pool, except
+ *     kv_yield_request / kv_yield_clear / kv_yield_pending, which are safe from
+ *     any thread at any time.
+ *
+ * Pool layout (bf16 elements, block-major so that a block-id range is an
+ * address range):   pool[block][layer][K=0|V=1][kv_head][slot][d]
+ * with block_tokens (= 16) slots per block.
+ */
+#ifndef VALVEKV_H
+#define VALVEKV_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define VKV_OK          0
+#define VKV_YIELDED     1   /* kv_attn_run_layer stopped at a slice boundary on request */
+#define VKV_E_INVAL    (-1) /* bad argument, misaligned or out-of-bounds range; nothing changed */
+#define VKV_E_NOSPACE  (-2) /* not enough free blocks; nothing changed */
+#define VKV_E_BUSY     (-3) /* range overlaps one that is already handed over; nothing changed */
+#define VKV_E_HIP      (-4) /* a HIP call failed; the pool must be destroyed */
+#define VKV_E_STATE    (-5) /* call sequence error (e.g. slice without a bound plan) or
+                               inconsistent tables found by a checker */
+
+typedef struct vkv_pool vkv_pool;
+
+/* Geometry of the shared KV pool: equal-size handles of blocks_per_handle
+ * blocks each (Section 3: a global pool of coarse handles with an
+ * allocate-release interface; Algorithm 1 requires equal-size handles). */
+typedef struct vkv_pool_config {
+  int32_t  num_layers;
+  int32_t  num_q_heads;
+  int32_t  num_kv_heads;        /* divides num_q_heads; group size G = q/kv <= 16 */
+  int32_t  head_dim;            /* 64 or 128 */
+  int32_t  block_tokens;        /* 16 */
+  int32_t  num_blocks;          /* NB; multiple of blocks_per_handle */
+  int32_t  blocks_per_handle;   /* reclaimed ranges are multiples of this */
+  int32_t  reserved;
+  void*    base;                /* device, 16-byte aligned, caller-owned; may be NULL for a
+                                   host-only pool that is never used for device work */
+  uint64_t bytes;               /* >= num_blocks * block_bytes */
+} vkv_pool_config;
+
+const char* vkv_last_error(void);
+
+/* ---- pool (host-only bookkeeping; no device work) ---------------------- */
+
+/* Validates the geometry and creates a pool in which every block is free.
+ * Errors: VKV_E_INVAL. */
+int kv_pool_init(const vkv_pool_config* cfg, vkv_pool** out);
+int kv_pool_destroy(vkv_pool* pool);
+
+/* Allocate-release interface (Section 3).  kv_pool_alloc hands out the n lowest
+ * free block ids outside handed-over ranges (VKV_E_NOSPACE if fewer exist);
+ * kv_pool_adopt marks the given free ids live (to build a fragmented state);
+ * kv_pool_free releases live ids.  A bad id gives VKV_E_INVAL and no change. */
+int kv_pool_alloc(vkv_pool* pool, int32_t n, int32_t* ids_out_host);
+int kv_pool_adopt(vkv_pool* pool, const int32_t* ids_host, int32_t n);
+int kv_pool_free(vkv_pool* pool, const int32_t* ids_host, int32_t n);
+
+/* The online tenant gives back a range obtained by kv_reclaim_range: its blocks
+ * become free pool blocks again.  VKV_E_INVAL if [lo,hi) is not exactly a
+ * handed-over range. */
+int kv_pool_return_range(vkv_pool* pool, int32_t lo_block, int32_t hi_block);
+
+/* State read-back: live_out_host[NB] gets 1 for live blocks; ranges_out_host
+ * gets up to cap (lo,hi) pairs of handed-over ranges, *n_ranges their count.
+ * Either output may be NULL. */
+int kv_pool_state(vkv_pool* pool, uint8_t* live_out_host,
+                  int32_t* ranges_out_host, int32_t cap, int32_t* n_ranges);
+
+/* Checks a host copy of block tables against the pool: every entry is -1 or a
+ * live block outside every handed-over range.  VKV_E_STATE on the first
+ * violation (message names entry and block). */
+int kv_pool_check_tables(vkv_pool* pool, const int32_t* tables_host, int64_t n_entries);
+
+/* ---- decode attention -------------------------------------------------- */
+
+typedef struct vkv_attn_plan_info {
+  int32_t  n_items;             /* work items = (sequence, kv head, chunk of tokens) */
+  int32_t  n_slices;            /* launches per layer */
+  uint64_t workspace_bytes;     /* device workspace the caller must provide */
+  uint64_t kv_bytes_per_layer;  /* K+V bytes one layer's attention reads */
+  uint64_t max_slice_kv_bytes;  /* largest slice */
+} vkv_attn_plan_info;
+
+/* Host only.  Cuts the decode batch into work items of at most chunk_tokens
+ * consecutive tokens of one kv head (order: sequence, chunk, kv head) and groups
+ * consecutive items into slices reading at most slice_bytes of K+V (at least
+ * one item each), so that a yield request is honoured within one slice
+ * (Section 2.3, Challenge 1: bounded preemption latency).
+ * ctx_len_host[s] >= 1 counts the tokens already in the cache, the newest
+ * included.  chunk_tokens: positive multiple of 32.  Replaces any earlier plan.
+ * Errors: VKV_E_INVAL. */
+int kv_attn_plan(vkv_pool* pool, const int32_t* ctx_len_host, int32_t num_seqs,
+                 uint64_t slice_bytes, int32_t chunk_tokens, vkv_attn_plan_info* info_out);
+
+/* Copies the current plan to host arrays: work_out_host[n_items][4] =
+ * (sequence, kv_head, first_block_index, n_tokens); slice_start_out_host[n_slices+1]. */
+int kv_attn_plan_read(vkv_pool* pool, int32_t* work_out_host, int32_t* slice_start_out_host);
+
+/* Enqueues the upload of the current plan into `workspace` (device,
+ * >= workspace_bytes, 256-byte aligned) on `stream`.  The workspace also holds
+ * the per-item partial results of one layer at a time; it is the resume state
+ * after a yield and must not be touched by the caller between slices of a layer.
+ * Blocks the host only if an earlier upload from the same pool is still in
+ * flight.  Errors: VKV_E_INVAL, VKV_E_STATE (no plan), VKV_E_HIP. */
+int kv_attn_bind(vkv_pool* pool, void* workspace, uint64_t workspace_bytes, void* stream);
+
+/* Enqueues one slice of one layer: for every work item of the slice, scores
+ * q.k/sqrt(D) (or * softmax_scale if nonzero) of the G query heads of the
+ * item's kv head against the item's tokens, running maximum, sum of
+ * exponentials and exp-weighted sum of V rows, written to the workspace.
+ * Query head g uses kv head g / G.  Token t of a sequence lives in block
+ * block_table[seq][t / 16], slot t % 16; slots past the sequence length are
+ * never read.  bf16 inputs, fp32 accumulation.
+ *   q_bf16       device [num_seqs][num_q_heads][head_dim] for this layer
+ *   block_table  device int32 [>= num_seqs rows][max_blk], -1 padded
+ * The host checks layer, slice and max_blk against the plan (VKV_E_INVAL,
+ * VKV_E_STATE); the kernel skips table entries outside [0, NB) and raises a flag
+ * that kv_attn_finalize's status word reports. */
+int paged_decode_attn_slice(vkv_pool* pool, int32_t layer, int32_t slice,
+                            const void* q_bf16, const int32_t* block_table, int32_t max_blk,
+                            void* workspace, float softmax_scale, void* stream);
+
+/* Enqueues the merge of the layer's partial results:
+ * out fp32 device [num_seqs][num_q_heads][head_dim].  Call after all slices of
+ * the layer have been enqueued on the same stream. */
+int kv_attn_finalize(vkv_pool* pool, void* workspace, void* out_f32, void* stream);
+
+/* Waits for `stream` and returns VKV_E_STATE if any slice since the last bind
+ * met a block-table entry outside [0, NB); VKV_OK otherwise. */
+int kv_attn_check(vkv_pool* pool, void* workspace, void* stream);
+
+/* Slice scheduler.  Issues slices *cursor_slice .. n_slices-1 of `layer`, then
+ * the merge, keeping at most max_inflight (1..8) slices enqueued ahead of the
+ * GPU so that the host stays close to the device.  Before each slice it tests
+ * the yield flag; if set it stops issuing, waits until the slices already
+ * enqueued have finished, stores the next slice in *cursor_slice and returns
+ * VKV_YIELDED: offline compute is then off the GPU.  A later call with the same
+ * cursor continues without recomputing anything (the paper's requirement that
+ * preempted work is resumed, not repeated: Section 2.2 on duplicated
+ * iterations; Section 4.1).  On VKV_OK *cursor_slice = n_slices and the merge
+ * has been enqueued (not waited for). */
+int kv_attn_run_layer(vkv_pool* pool, int32_t layer, int32_t* cursor_slice,
+                      const void* q_bf16, const int32_t* block_table, int32_t max_blk,
+                      void* workspace, void* out_f32, float softmax_scale,
+                      int32_t max_inflight, void* stream);
+
+/* Yield flag (the online tenant's "busy" edge of Section 4.2).  Thread-safe. */
+int kv_yield_request(vkv_pool* pool);
+int kv_yield_clear(vkv_pool* pool);
+int kv_yield_pending(vkv_pool* pool);   /* 1 if set, 0 if not */
+
+/* ---- reclamation ------------------------------------------------------- */
+
+typedef struct vkv_reclaim_stats {
+  uint64_t bytes_moved;         /* live bytes copied (read side) */
+  int32_t  blocks_moved;
+  int32_t  blocks_in_range;     /* hi - lo */
+  int32_t  n_chunks;            /* copy launches */
+  int32_t  reserved;
+  double   host_seconds;        /* wall time of the call */
+} vkv_reclaim_stats;
+
+/* Host only, changes nothing.  Plans the relocation of range [lo,hi): the i-th
+ * live block of the range (ascending) goes to the i-th free block (ascending)
+ * outside the range and outside every handed-over range.  remap_out_host[NB]
+ * (may be NULL) gets the identity except remap[src_i] = dst_i.
+ * Errors: VKV_E_INVAL (range empty, out of bounds or not handle-aligned),
+ * VKV_E_BUSY, VKV_E_NOSPACE. */
+int kv_reclaim_plan(vkv_pool* pool, int32_t lo_block, int32_t hi_block,
+                    int32_t* remap_out_host, vkv_reclaim_stats* stats_out);
+
+#define VKV_RECLAIM_ASYNC 1u  /* return after enqueueing; the caller waits for copy_stream
+                                 and guarantees that no slice is in flight */
+
+/* Hands block range [lo,hi) to the online tenant (Section 5: stop offline
+ * compute first, pick handles, make them harmless, hand them over):
+ *   1. plan as kv_reclaim_plan; on error nothing has changed;
+ *   2. copy live blocks out of the range on copy_stream, in launches of at most
+ *      chunk_bytes of live data (0 = one launch); with rate_cap_bytes_per_s > 0
+ *      launch j is not issued before t0 + (live bytes of launches < j) / cap
+ *      (the host thread sleeps; burst allowance = one chunk);
+ *   3. rewrite block_tables (device int32, n_entries entries, -1 = empty) in
+ *      place: entry e becomes remap[e];
+ *   4. wait for copy_stream; if decode_stream is given, wait until the slices
+ *      that were enqueued on it so far have finished (they may have read old
+ *      entries, which still point at intact source blocks);
+ *   5. mark the range handed over.  From here no table entry and no later
+ *      slice refers to it.
+ * remap_dev: device int32 [NB] scratch, filled with the remap of this call.
+ * With VKV_RECLAIM_ASYNC step 4 is skipped.
+ * Concurrent slices on decode_stream stay correct throughout: copies only write
+ * free blocks, and both old and new table entries name identical bytes.
+ * Errors: as kv_reclaim_plan, VKV_E_HIP. */
+int kv_reclaim_range(vkv_pool* pool, int32_t lo_block, int32_t hi_block,
+                     int32_t* block_tables, int64_t n_entries,
+                     uint64_t chunk_bytes, uint64_t rate_cap_bytes_per_s,
+                     void* copy_stream, void* decode_stream,
+                     int32_t* remap_dev, uint32_t flags, vkv_reclaim_stats* stats_out);
+
+/* Enqueues tables[i] = remap[tables[i]] for every entry in [0, num_blocks);
+ * other entries (-1 padding) are left alone.  Exported on its own for tables the
+ * pool does not know about (Section 5: the framework is told which block ids
+ * changed). */
+int block_table_rewrite(int32_t* tables_dev, int64_t n_entries, const int32_t* remap_dev,
+                        int32_t num_blocks, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VALVEKV_H */

@@ -1,0 +1,264 @@
+"""ctypes binding: same names as the C ABI, argument marshalling only.
+
+Device arguments are torch tensors (their data_ptr is passed) or raw integer
+addresses; host arguments are numpy arrays.  Streams are torch.cuda.Stream
+objects, raw hipStream_t integers, or None for torch's current stream.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import numpy as np
+
+__all__ = [
+    "VKV_OK", "VKV_YIELDED", "VKV_E_INVAL", "VKV_E_NOSPACE", "VKV_E_BUSY", "VKV_E_HIP", "VKV_E_STATE",
+    "VKV_RECLAIM_ASYNC", "VkvError", "PoolConfig", "AttnPlanInfo", "ReclaimStats", "lib", "library_path",
+    "last_error", "kv_pool_init", "kv_pool_destroy", "kv_pool_alloc", "kv_pool_adopt", "kv_pool_free",
+    "kv_pool_return_range", "kv_pool_state", "kv_pool_check_tables", "kv_attn_plan", "kv_attn_plan_read",
+    "kv_attn_bind", "paged_decode_attn_slice", "kv_attn_finalize", "kv_attn_check", "kv_attn_run_layer",
+    "kv_yield_request", "kv_yield_clear", "kv_yield_pending", "kv_reclaim_plan", "kv_reclaim_range",
+    "block_table_rewrite",
+]
+
+VKV_OK, VKV_YIELDED = 0, 1
+VKV_E_INVAL, VKV_E_NOSPACE, VKV_E_BUSY, VKV_E_HIP, VKV_E_STATE = -1, -2, -3, -4, -5
+VKV_RECLAIM_ASYNC = 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, "libvalvekv.so")
+
+
+class VkvError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"valvekv error {code}: {msg}")
+        self.code = code
+
+
+class PoolConfig(C.Structure):
+    _fields_ = [("num_layers", C.c_int32), ("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("block_tokens", C.c_int32), ("num_blocks", C.c_int32),
+                ("blocks_per_handle", C.c_int32), ("reserved", C.c_int32),
+                ("base", C.c_void_p), ("bytes", C.c_uint64)]
+
+
+class AttnPlanInfo(C.Structure):
+    _fields_ = [("n_items", C.c_int32), ("n_slices", C.c_int32), ("workspace_bytes", C.c_uint64),
+                ("kv_bytes_per_layer", C.c_uint64), ("max_slice_kv_bytes", C.c_uint64)]
+
+
+class ReclaimStats(C.Structure):
+    _fields_ = [("bytes_moved", C.c_uint64), ("blocks_moved", C.c_int32), ("blocks_in_range", C.c_int32),
+                ("n_chunks", C.c_int32), ("reserved", C.c_int32), ("host_seconds", C.c_double)]
+
+
+def _load():
+    path = library_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: build it with `python -m paper_2604_07874_amd.build` "
+                          "(there is no fallback path)")
+    return C.CDLL(path)
+
+
+lib = _load()
+
+_P = C.c_void_p
+_I32P = C.POINTER(C.c_int32)
+_sigs = {
+    "vkv_last_error": (C.c_char_p, []),
+    "kv_pool_init": (C.c_int, [C.POINTER(PoolConfig), C.POINTER(_P)]),
+    "kv_pool_destroy": (C.c_int, [_P]),
+    "kv_pool_alloc": (C.c_int, [_P, C.c_int32, _P]),
+    "kv_pool_adopt": (C.c_int, [_P, _P, C.c_int32]),
+    "kv_pool_free": (C.c_int, [_P, _P, C.c_int32]),
+    "kv_pool_return_range": (C.c_int, [_P, C.c_int32, C.c_int32]),
+    "kv_pool_state": (C.c_int, [_P, _P, _P, C.c_int32, _I32P]),
+    "kv_pool_check_tables": (C.c_int, [_P, _P, C.c_int64]),
+    "kv_attn_plan": (C.c_int, [_P, _P, C.c_int32, C.c_uint64, C.c_int32, C.POINTER(AttnPlanInfo)]),
+    "kv_attn_plan_read": (C.c_int, [_P, _P, _P]),
+    "kv_attn_bind": (C.c_int, [_P, _P, C.c_uint64, _P]),
+    "paged_decode_attn_slice": (C.c_int, [_P, C.c_int32, C.c_int32, _P, _P, C.c_int32, _P, C.c_float, _P]),
+    "kv_attn_finalize": (C.c_int, [_P, _P, _P, _P]),
+    "kv_attn_check": (C.c_int, [_P, _P, _P]),
+    "kv_attn_run_layer": (C.c_int, [_P, C.c_int32, _I32P, _P, _P, C.c_int32, _P, _P, C.c_float, C.c_int32, _P]),
+    "kv_yield_request": (C.c_int, [_P]),
+    "kv_yield_clear": (C.c_int, [_P]),
+    "kv_yield_pending": (C.c_int, [_P]),
+    "kv_reclaim_plan": (C.c_int, [_P, C.c_int32, C.c_int32, _P, C.POINTER(ReclaimStats)]),
+    "kv_reclaim_range": (C.c_int, [_P, C.c_int32, C.c_int32, _P, C.c_int64, C.c_uint64, C.c_uint64, _P, _P, _P,
+                                   C.c_uint32, C.POINTER(ReclaimStats)]),
+    "block_table_rewrite": (C.c_int, [_P, C.c_int64, _P, C.c_int32, _P]),
+}
+for _name, (_res, _args) in _sigs.items():
+    _fn = getattr(lib, _name)
+    _fn.restype = _res
+    _fn.argtypes = _args
+
+
+def last_error() -> str:
+    return lib.vkv_last_error().decode()
+
+
+def _check(code: int, ok=(VKV_OK,)):
+    if code not in ok:
+        raise VkvError(code, last_error())
+    return code
+
+
+def _dev(x) -> Optional[int]:
+    """Device address of a torch tensor, or an int address, or None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    assert x.is_cuda and x.is_contiguous(), "device arguments must be contiguous device tensors"
+    return x.data_ptr()
+
+
+def _host(a: np.ndarray, dtype) -> np.ndarray:
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+def _stream(s) -> Optional[int]:
+    if s is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(s, int):
+        return s or None
+    return s.cuda_stream or None
+
+
+# ---- pool -------------------------------------------------------------------------
+def kv_pool_init(num_layers, num_q_heads, num_kv_heads, head_dim, num_blocks, blocks_per_handle,
+                 base=None, nbytes=0, block_tokens=16):
+    """base: torch tensor holding the pool (or None for a host-only pool).  Returns the pool handle."""
+    cfg = PoolConfig(num_layers, num_q_heads, num_kv_heads, head_dim, block_tokens, num_blocks,
+                     blocks_per_handle, 0, _dev(base),
+                     nbytes if isinstance(base, int) or base is None else base.numel() * base.element_size())
+    out = _P()
+    _check(lib.kv_pool_init(C.byref(cfg), C.byref(out)))
+    return out
+
+
+def kv_pool_destroy(pool):
+    _check(lib.kv_pool_destroy(pool))
+
+
+def kv_pool_alloc(pool, n: int) -> np.ndarray:
+    ids = np.empty(n, dtype=np.int32)
+    _check(lib.kv_pool_alloc(pool, n, ids.ctypes.data))
+    return ids
+
+
+def kv_pool_adopt(pool, ids):
+    ids = _host(ids, np.int32)
+    _check(lib.kv_pool_adopt(pool, ids.ctypes.data, len(ids)))
+
+
+def kv_pool_free(pool, ids):
+    ids = _host(ids, np.int32)
+    _check(lib.kv_pool_free(pool, ids.ctypes.data, len(ids)))
+
+
+def kv_pool_return_range(pool, lo: int, hi: int):
+    _check(lib.kv_pool_return_range(pool, lo, hi))
+
+
+def kv_pool_state(pool, num_blocks: int, max_ranges: int = 64):
+    """Returns (live uint8[NB], list of handed-over (lo, hi))."""
+    live = np.empty(num_blocks, dtype=np.uint8)
+    ranges = np.empty(2 * max_ranges, dtype=np.int32)
+    n = C.c_int32(0)
+    _check(lib.kv_pool_state(pool, live.ctypes.data, ranges.ctypes.data, max_ranges, C.byref(n)))
+    k = min(n.value, max_ranges)
+    return live, [(int(ranges[2 * i]), int(ranges[2 * i + 1])) for i in range(k)]
+
+
+def kv_pool_check_tables(pool, tables_host):
+    t = _host(tables_host, np.int32)
+    _check(lib.kv_pool_check_tables(pool, t.ctypes.data, t.size))
+
+
+# ---- attention --------------------------------------------------------------------
+def kv_attn_plan(pool, ctx_len_host, slice_bytes: int, chunk_tokens: int) -> AttnPlanInfo:
+    ctx = _host(ctx_len_host, np.int32)
+    info = AttnPlanInfo()
+    _check(lib.kv_attn_plan(pool, ctx.ctypes.data, len(ctx), slice_bytes, chunk_tokens, C.byref(info)))
+    return info
+
+
+def kv_attn_plan_read(pool, info: AttnPlanInfo):
+    work = np.empty((info.n_items, 4), dtype=np.int32)
+    starts = np.empty(info.n_slices + 1, dtype=np.int32)
+    _check(lib.kv_attn_plan_read(pool, work.ctypes.data, starts.ctypes.data))
+    return work, starts
+
+
+def kv_attn_bind(pool, workspace, stream=None):
+    _check(lib.kv_attn_bind(pool, _dev(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def paged_decode_attn_slice(pool, layer: int, slice_idx: int, q, block_table, workspace,
+                            softmax_scale: float = 0.0, stream=None):
+    _check(lib.paged_decode_attn_slice(pool, layer, slice_idx, _dev(q), _dev(block_table), block_table.shape[-1],
+                                       _dev(workspace), softmax_scale, _stream(stream)))
+
+
+def kv_attn_finalize(pool, workspace, out, stream=None):
+    _check(lib.kv_attn_finalize(pool, _dev(workspace), _dev(out), _stream(stream)))
+
+
+def kv_attn_check(pool, workspace, stream=None):
+    _check(lib.kv_attn_check(pool, _dev(workspace), _stream(stream)))
+
+
+def kv_attn_run_layer(pool, layer: int, cursor: int, q, block_table, workspace, out,
+                      softmax_scale: float = 0.0, max_inflight: int = 2, stream=None):
+    """Returns (status, cursor): status VKV_OK or VKV_YIELDED."""
+    cur = C.c_int32(cursor)
+    st = lib.kv_attn_run_layer(pool, layer, C.byref(cur), _dev(q), _dev(block_table), block_table.shape[-1],
+                               _dev(workspace), _dev(out), softmax_scale, max_inflight, _stream(stream))
+    _check(st, ok=(VKV_OK, VKV_YIELDED))
+    return st, cur.value
+
+
+def kv_yield_request(pool):
+    _check(lib.kv_yield_request(pool))
+
+
+def kv_yield_clear(pool):
+    _check(lib.kv_yield_clear(pool))
+
+
+def kv_yield_pending(pool) -> bool:
+    return bool(lib.kv_yield_pending(pool))
+
+
+# ---- reclamation ------------------------------------------------------------------
+def kv_reclaim_plan(pool, lo: int, hi: int, num_blocks: int):
+    """Dry run.  Returns (remap int32[NB], stats)."""
+    remap = np.empty(num_blocks, dtype=np.int32)
+    stats = ReclaimStats()
+    _check(lib.kv_reclaim_plan(pool, lo, hi, remap.ctypes.data, C.byref(stats)))
+    return remap, stats
+
+
+def kv_reclaim_range(pool, lo: int, hi: int, block_tables, remap_dev, chunk_bytes: int = 0,
+                     rate_cap_bytes_per_s: int = 0, copy_stream=None, decode_stream=None,
+                     flags: int = 0) -> ReclaimStats:
+    stats = ReclaimStats()
+    ds = None if decode_stream is None else _stream(decode_stream)
+    _check(lib.kv_reclaim_range(pool, lo, hi, _dev(block_tables), block_tables.numel(), chunk_bytes,
+                                int(rate_cap_bytes_per_s), _stream(copy_stream), ds, _dev(remap_dev), flags,
+                                C.byref(stats)))
+    return stats
+
+
+def block_table_rewrite(block_tables, remap_dev, num_blocks: int, stream=None):
+    _check(lib.block_table_rewrite(_dev(block_tables), block_tables.numel(), _dev(remap_dev), num_blocks,
+                                   _stream(stream)))

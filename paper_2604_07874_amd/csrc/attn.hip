@@ -1,0 +1,513 @@
+// Preemptible decode attention over the paged bf16 KV pool.
+//
+// One layer's attention is cut into work items (sequence, kv head, chunk of tokens) and
+// the items into slices of bounded KV bytes; each slice is one launch, so a yield lands
+// at a slice boundary (the sub-millisecond bound of paper Section 2.3, Challenge 1 and
+// Section 4.1, met without a driver).  The kernel is HBM-bound: it reads every K and V
+// byte of its tokens once; the MFMA units do the GQA q.K and p.V tiles.
+//
+// Kernel shape (wave64, gfx950):
+//   workgroup = 4 waves = one work item; wave w takes the 32-token groups w, w+4, ...
+//   Per group a wave issues 16 coalesced 16-byte-per-lane loads (K and V rows of two
+//   blocks): lane (c = lane%16, kg = lane/16) gets bytes [16c,16c+16) of rows kg, 4+kg,
+//   8+kg, 12+kg of each block.
+//   K rows go through a per-wave LDS tile to reach the A-operand layout of
+//   v_mfma_f32_16x16x32_bf16 (row = token, 8 consecutive d per lane); the B operand is q,
+//   one query head per column, columns >= G zero.
+//   Scores come back with column = query head = lane%16 and rows kg*4..kg*4+3; tokens are
+//   assigned to rows so that row kg*4+r is the token the same lane group loaded as its
+//   r-th V row.  The V registers therefore feed the second MFMA (out^T = V^T . P^T)
+//   straight from the loads after an in-register 16-bit transpose, with no LDS traffic:
+//   lane c owns output dims {c*D/16 + dt}.
+//   Softmax statistics are per lane (= per query head): running max m (log2 units), sum l,
+//   and the accumulator is rescaled when m grows.  l is summed from the bf16-rounded
+//   weights that enter the MFMA, so the result is an exact convex combination of V rows.
+#include "vkv_internal.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+
+namespace vkv {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+struct AttnParams {
+  const uint16_t* pool;      // pool base + layer offset (elements)
+  const WorkItem* work;      // device
+  const uint16_t* q;         // [S][Hq][D]
+  const int32_t* table;      // [rows][max_blk]
+  float* part_acc;           // [n_items][G][D]
+  float* part_ml;            // [n_items][G][2]
+  uint32_t* err;             // workspace header word 0
+  uint64_t block_elems;
+  uint32_t v_off;            // elements from a block's K plane to its V plane (one layer)
+  int32_t item_first;
+  int32_t max_blk;
+  int32_t Hq, G, NB;
+  float scale_log2;          // softmax scale * log2(e)
+};
+
+template <int D> struct LdVec;
+template <> struct LdVec<128> { using type = u32x4; };
+template <> struct LdVec<64> { using type = u32x2; };
+
+// word j of a lane-row register as 32 bits (two bf16)
+__device__ __forceinline__ uint32_t word_of(const u32x4& v, int j) { return v[j]; }
+__device__ __forceinline__ uint32_t word_of(const u32x2& v, int j) { return v[j]; }
+
+template <int D>
+__global__ __launch_bounds__(256, 2) void paged_decode_attn_slice_kernel(const AttnParams p) {
+  using ldvec = typename LdVec<D>::type;
+  constexpr int EPL = D / 16;          // bf16 per lane per row (8 or 4)
+  constexpr int KS = D / 32;           // MFMA k-steps of the score tile
+  constexpr int RS = D * 2 + 16;       // LDS row stride in bytes (padded against bank conflicts)
+  constexpr int TILE = 32 * RS;        // one wave's K tile
+  constexpr float NEG_INF = -INFINITY;
+
+  __shared__ __attribute__((aligned(16))) unsigned char lds[4 * TILE];
+  __shared__ float sm_m[4][16], sm_l[4][16];
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int c16 = lane & 15, kg = lane >> 4;
+
+  const WorkItem it = p.work[p.item_first + blockIdx.x];
+  const int ntok = it.n_tokens;
+  const int ngroups = (ntok + kGroupTokens - 1) / kGroupTokens;
+  const int G = p.G;
+
+  // B operand of the score MFMA: column = query head, k index kg*8+j <-> d = 32*ks + 8*kg + j
+  bf16x8 qb[KS];
+  {
+    const bool valid = c16 < G;
+    const uint16_t* qrow = p.q + ((size_t)it.seq * p.Hq + (size_t)it.kv_head * G + (valid ? c16 : 0)) * D;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (valid) v = *reinterpret_cast<const u32x4*>(qrow + ks * 32 + kg * 8);
+      qb[ks] = __builtin_bit_cast(bf16x8, v);
+    }
+  }
+
+  const int32_t* trow = p.table + (size_t)it.seq * p.max_blk + it.first_block;
+  const uint16_t* kplane = p.pool + (size_t)it.kv_head * (16 * D);
+  unsigned char* tile = lds + wave * TILE;
+
+  f32x4 acc[EPL];
+#pragma unroll
+  for (int dt = 0; dt < EPL; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m_run = NEG_INF, l_run = 0.f;
+
+  ldvec kr[8], vr[8];   // [block b of the group][row slot r]: row 4r+kg of block b
+
+  auto issue = [&](int grp) {
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      const int bi = grp * 2 + b;
+      const bool have = bi * 16 < ntok;
+      int32_t blk = have ? trow[bi] : -1;
+      blk = __builtin_amdgcn_readfirstlane(blk);
+      if (blk < 0 || blk >= p.NB) {
+        if (have && lane == 0) atomicOr(p.err, 1u);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          kr[b * 4 + r] = ldvec{};
+          vr[b * 4 + r] = ldvec{};
+        }
+      } else {
+        const ldvec* ks = reinterpret_cast<const ldvec*>(kplane + (size_t)blk * p.block_elems);
+        const ldvec* vs = reinterpret_cast<const ldvec*>(kplane + (size_t)blk * p.block_elems + p.v_off);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) kr[b * 4 + r] = ks[r * 64 + lane];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) vr[b * 4 + r] = vs[r * 64 + lane];
+      }
+    }
+  };
+
+  int grp = wave;
+  if (grp < ngroups) issue(grp);
+
+  for (; grp < ngroups; grp += 4) {
+    const int tok0 = grp * kGroupTokens;
+    const bool tail = tok0 + kGroupTokens > ntok;
+
+    // K rows -> LDS tile, row index = 16b + 4r + kg, 16-byte column c16
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        *reinterpret_cast<ldvec*>(tile + (b * 16 + 4 * r + kg) * RS + c16 * (EPL * 2)) = kr[b * 4 + r];
+
+    // V rows past the end of the sequence may hold anything (NaN included): zero them
+    if (tail) {
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (tok0 + b * 16 + 4 * r + kg >= ntok) vr[b * 4 + r] = ldvec{};
+    }
+
+    // A operands of the second MFMA: va[dt] = element dt of each of the lane's 8 V rows
+    bf16x8 va[EPL];
+#pragma unroll
+    for (int dt = 0; dt < EPL; ++dt) {
+      u32x4 w;
+      const uint32_t sel = (dt & 1) ? 0x07060302u : 0x05040100u;   // high or low halves of (hi=src0, lo=src1)
+#pragma unroll
+      for (int pr = 0; pr < 4; ++pr)
+        w[pr] = __builtin_amdgcn_perm(word_of(vr[2 * pr + 1], dt >> 1), word_of(vr[2 * pr], dt >> 1), sel);
+      va[dt] = __builtin_bit_cast(bf16x8, w);
+    }
+
+    const int next = grp + 4;
+    if (next < ngroups) issue(next);
+
+    // LDS operations of one wave execute in order; keep the compiler from reordering them
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    // scores: tile b, MFMA row i <-> token 4*(i%4) + i/4 of block b
+    f32x4 sc[2];
+    const int trow_lds = 4 * (c16 & 3) + (c16 >> 2);
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      sc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const u32x4 a = *reinterpret_cast<const u32x4*>(tile + (b * 16 + trow_lds) * RS + (ks * 4 + kg) * 16);
+        sc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), qb[ks], sc[b], 0, 0, 0);
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+
+    // this lane: query head c16, tokens tok0 + 16b + 4r + kg
+    float x[8];
+    float mx = NEG_INF;
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const bool ok = !tail || (tok0 + b * 16 + 4 * r + kg < ntok);
+        const float v = ok ? sc[b][r] * p.scale_log2 : NEG_INF;
+        x[b * 4 + r] = v;
+        mx = fmaxf(mx, v);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m_run, mx);           // finite: every group holds a valid token
+    const float alpha = __builtin_exp2f(m_run - m_new);
+    bf16x8 pb;
+    float psum = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const __bf16 pj = (__bf16)__builtin_exp2f(x[j] - m_new);
+      pb[j] = pj;
+      psum += (float)pj;
+    }
+    l_run = l_run * alpha + psum;
+    m_run = m_new;
+#pragma unroll
+    for (int dt = 0; dt < EPL; ++dt) {
+      acc[dt] *= alpha;
+      acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pb, acc[dt], 0, 0, 0);
+    }
+  }
+
+  // ---- merge the four waves (each covered a disjoint subset of the item's tokens) ----
+  l_run += __shfl_xor(l_run, 16);
+  l_run += __shfl_xor(l_run, 32);
+  __syncthreads();   // all waves are done with their K tiles
+  float* macc = reinterpret_cast<float*>(lds);   // [4][G][D]
+  if (c16 < G) {
+#pragma unroll
+    for (int dt = 0; dt < EPL; ++dt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        macc[((size_t)wave * G + c16) * D + (kg * 4 + r) * EPL + dt] = acc[dt][r];
+    if (kg == 0) {
+      sm_m[wave][c16] = m_run;
+      sm_l[wave][c16] = l_run;
+    }
+  }
+  __syncthreads();
+  const size_t item = (size_t)p.item_first + blockIdx.x;
+  for (int e = threadIdx.x; e < G * D; e += 256) {
+    const int g = e / D, d = e - g * D;
+    float M = sm_m[0][g];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) M = fmaxf(M, sm_m[w][g]);
+    float num = 0.f, den = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float wt = __builtin_exp2f(sm_m[w][g] - M);   // 0 for a wave that had no group
+      num += wt * macc[((size_t)w * G + g) * D + d];
+      den += wt * sm_l[w][g];
+    }
+    p.part_acc[(item * G + g) * D + d] = num;
+    if (d == 0) {
+      p.part_ml[(item * G + g) * 2 + 0] = M;
+      p.part_ml[(item * G + g) * 2 + 1] = den;
+    }
+  }
+}
+
+// out[s][h*G+g][:] = sum_c 2^(m_c - M) acc_c / sum_c 2^(m_c - M) l_c over the chunks c of (s, h).
+__global__ __launch_bounds__(256) void attn_combine_kernel(const float* __restrict__ part_acc,
+                                                           const float* __restrict__ part_ml,
+                                                           const int32_t* __restrict__ seq_base, float* __restrict__ out,
+                                                           int Hkv, int G, int D) {
+  const int s = blockIdx.x / Hkv, h = blockIdx.x - s * Hkv;
+  const int base = seq_base[s];
+  const int nch = (seq_base[s + 1] - base) / Hkv;
+  for (int e = threadIdx.x; e < G * D; e += 256) {
+    const int g = e / D, d = e - g * D;
+    float M = -INFINITY;
+    for (int c = 0; c < nch; ++c) M = fmaxf(M, part_ml[(((size_t)base + (size_t)c * Hkv + h) * G + g) * 2]);
+    float num = 0.f, den = 0.f;
+    for (int c = 0; c < nch; ++c) {
+      const size_t ig = ((size_t)base + (size_t)c * Hkv + h) * G + g;
+      const float wt = __builtin_exp2f(part_ml[ig * 2] - M);
+      num += wt * part_acc[ig * D + d];
+      den += wt * part_ml[ig * 2 + 1];
+    }
+    out[((size_t)s * Hkv * G + (size_t)h * G + g) * D + d] = num / den;
+  }
+}
+
+// ---- host ---------------------------------------------------------------------------
+
+static int check_bound(vkv_pool* p, const void* workspace, const char* who) {
+  if (!p) { set_error("%s: null pool", who); return VKV_E_INVAL; }
+  if (p->broken) { set_error("%s: pool unusable after a HIP failure", who); return VKV_E_HIP; }
+  if (!p->has_plan) { set_error("%s: no plan; call kv_attn_plan first", who); return VKV_E_STATE; }
+  if (!workspace || workspace != p->bound_ws || p->bound_gen != p->plan_gen) {
+    set_error("%s: workspace is not bound to the current plan; call kv_attn_bind", who);
+    return VKV_E_STATE;
+  }
+  return VKV_OK;
+}
+
+static int launch_slice(vkv_pool* p, int32_t layer, int32_t slice, const void* q, const int32_t* table,
+                        int32_t max_blk, void* workspace, float scale, hipStream_t st) {
+  const int32_t first = p->slice_start[slice], count = p->slice_start[slice + 1] - first;
+  const int D = p->cfg.head_dim;
+  char* ws = (char*)workspace;
+  AttnParams a;
+  const uint64_t layer_elems = (uint64_t)2 * p->cfg.num_kv_heads * 16 * D;
+  a.pool = (const uint16_t*)p->cfg.base + (uint64_t)layer * layer_elems;
+  a.work = (const WorkItem*)(ws + p->ws.work);
+  a.q = (const uint16_t*)q;
+  a.table = table;
+  a.part_acc = (float*)(ws + p->ws.part_acc);
+  a.part_ml = (float*)(ws + p->ws.part_ml);
+  a.err = (uint32_t*)(ws + p->ws.header);
+  a.block_elems = p->block_elems;
+  a.v_off = (uint32_t)(p->cfg.num_kv_heads * 16 * D);
+  a.item_first = first;
+  a.max_blk = max_blk;
+  a.Hq = p->cfg.num_q_heads;
+  a.G = p->G;
+  a.NB = p->cfg.num_blocks;
+  a.scale_log2 = (scale != 0.f ? scale : 1.0f / std::sqrt((float)D)) * 1.4426950408889634f;
+  if (D == 128)
+    hipLaunchKernelGGL(paged_decode_attn_slice_kernel<128>, dim3((unsigned)count), dim3(256), 0, st, a);
+  else
+    hipLaunchKernelGGL(paged_decode_attn_slice_kernel<64>, dim3((unsigned)count), dim3(256), 0, st, a);
+  VKV_HIP(hipGetLastError());
+  return VKV_OK;
+}
+
+static int check_slice_args(vkv_pool* p, int32_t layer, const void* q, const int32_t* table, int32_t max_blk,
+                            void* workspace, const char* who) {
+  int st = check_bound(p, workspace, who);
+  if (st != VKV_OK) return st;
+  if (!p->cfg.base) { set_error("%s: pool has no device memory", who); return VKV_E_INVAL; }
+  if (layer < 0 || layer >= p->cfg.num_layers) { set_error("%s: layer %d out of range", who, layer); return VKV_E_INVAL; }
+  if (!q || !table || (uintptr_t)q % 16) { set_error("%s: q (16-byte aligned) and block_table must be given", who); return VKV_E_INVAL; }
+  if (max_blk < p->max_ctx_blocks) {
+    set_error("%s: block table has %d columns, the plan needs %d", who, max_blk, p->max_ctx_blocks);
+    return VKV_E_INVAL;
+  }
+  return VKV_OK;
+}
+
+static int launch_finalize(vkv_pool* p, void* workspace, void* out, hipStream_t st) {
+  char* ws = (char*)workspace;
+  hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)(p->num_seqs * p->cfg.num_kv_heads)), dim3(256), 0, st,
+                     (const float*)(ws + p->ws.part_acc), (const float*)(ws + p->ws.part_ml),
+                     (const int32_t*)(ws + p->ws.seq_base), (float*)out, p->cfg.num_kv_heads, p->G, p->cfg.head_dim);
+  VKV_HIP(hipGetLastError());
+  return VKV_OK;
+}
+
+}  // namespace vkv
+
+using namespace vkv;
+
+extern "C" {
+
+int kv_attn_plan(vkv_pool* p, const int32_t* ctx, int32_t S, uint64_t slice_bytes, int32_t chunk_tokens,
+                 vkv_attn_plan_info* info) {
+  if (!p || !ctx || S < 1) { set_error("kv_attn_plan: bad argument"); return VKV_E_INVAL; }
+  if (chunk_tokens < kGroupTokens || chunk_tokens % kGroupTokens) {
+    set_error("kv_attn_plan: chunk_tokens must be a positive multiple of %d", kGroupTokens);
+    return VKV_E_INVAL;
+  }
+  const int Hkv = p->cfg.num_kv_heads, D = p->cfg.head_dim, B = p->cfg.block_tokens;
+  int64_t n_items = 0;
+  int32_t max_blocks = 0;
+  for (int32_t s = 0; s < S; ++s) {
+    if (ctx[s] < 1) { set_error("kv_attn_plan: sequence %d has context length %d (< 1)", s, ctx[s]); return VKV_E_INVAL; }
+    n_items += (int64_t)((ctx[s] + chunk_tokens - 1) / chunk_tokens) * Hkv;
+    max_blocks = std::max(max_blocks, (ctx[s] + B - 1) / B);
+  }
+  if (n_items > 0x7FFFFFF0ll) { set_error("kv_attn_plan: too many work items"); return VKV_E_INVAL; }
+  std::vector<WorkItem> work;
+  std::vector<int32_t> seq_base((size_t)S + 1);
+  work.reserve((size_t)n_items);
+  for (int32_t s = 0; s < S; ++s) {
+    seq_base[s] = (int32_t)work.size();
+    for (int32_t first = 0; first < ctx[s]; first += chunk_tokens) {
+      const int32_t nt = std::min(chunk_tokens, ctx[s] - first);
+      for (int32_t h = 0; h < Hkv; ++h) work.push_back(WorkItem{s, h, first / B, nt});
+    }
+  }
+  seq_base[S] = (int32_t)work.size();
+  const uint64_t token_bytes = (uint64_t)2 * D * 2;
+  std::vector<int32_t> starts{0};
+  uint64_t acc = 0, total = 0, max_slice = 0;
+  for (size_t i = 0; i < work.size(); ++i) {
+    const uint64_t b = (uint64_t)work[i].n_tokens * token_bytes;
+    if ((int32_t)i > starts.back() && acc + b > slice_bytes) {
+      max_slice = std::max(max_slice, acc);
+      starts.push_back((int32_t)i);
+      acc = 0;
+    }
+    acc += b;
+    total += b;
+  }
+  max_slice = std::max(max_slice, acc);
+  starts.push_back((int32_t)work.size());
+
+  p->work.swap(work);
+  p->slice_start.swap(starts);
+  p->seq_base.swap(seq_base);
+  p->num_seqs = S;
+  p->chunk_tokens = chunk_tokens;
+  p->max_ctx_blocks = max_blocks;
+  p->ws = workspace_layout((int64_t)p->work.size(), S, p->G, D);
+  p->has_plan = true;
+  ++p->plan_gen;
+  if (info) {
+    info->n_items = (int32_t)p->work.size();
+    info->n_slices = (int32_t)p->slice_start.size() - 1;
+    info->workspace_bytes = p->ws.total;
+    info->kv_bytes_per_layer = total;
+    info->max_slice_kv_bytes = max_slice;
+  }
+  return VKV_OK;
+}
+
+int kv_attn_plan_read(vkv_pool* p, int32_t* work_out, int32_t* slice_start_out) {
+  if (!p) { set_error("kv_attn_plan_read: null pool"); return VKV_E_INVAL; }
+  if (!p->has_plan) { set_error("kv_attn_plan_read: no plan"); return VKV_E_STATE; }
+  if (work_out) std::memcpy(work_out, p->work.data(), p->work.size() * sizeof(WorkItem));
+  if (slice_start_out) std::memcpy(slice_start_out, p->slice_start.data(), p->slice_start.size() * 4);
+  return VKV_OK;
+}
+
+int kv_attn_bind(vkv_pool* p, void* workspace, uint64_t workspace_bytes, void* stream) {
+  if (!p) { set_error("kv_attn_bind: null pool"); return VKV_E_INVAL; }
+  if (p->broken) { set_error("kv_attn_bind: pool unusable after a HIP failure"); return VKV_E_HIP; }
+  if (!p->has_plan) { set_error("kv_attn_bind: no plan"); return VKV_E_STATE; }
+  if (!workspace || (uintptr_t)workspace % 256 || workspace_bytes < p->ws.total) {
+    set_error("kv_attn_bind: workspace must be 256-byte aligned and hold %llu bytes",
+              (unsigned long long)p->ws.total);
+    return VKV_E_INVAL;
+  }
+  int st = ensure_stage(p, p->ws.upload_bytes);
+  if (st != VKV_OK) return st;
+  char* h = (char*)p->stage;
+  std::memset(h, 0, 256);
+  std::memcpy(h + p->ws.work, p->work.data(), p->work.size() * sizeof(WorkItem));
+  std::memcpy(h + p->ws.seq_base, p->seq_base.data(), p->seq_base.size() * 4);
+  VKV_HIP(hipMemcpyAsync(workspace, h, p->ws.upload_bytes, hipMemcpyHostToDevice, (hipStream_t)stream));
+  VKV_HIP(hipEventRecord(p->stage_ev, (hipStream_t)stream));
+  p->stage_inflight = true;
+  p->bound_ws = workspace;
+  p->bound_gen = p->plan_gen;
+  return VKV_OK;
+}
+
+int paged_decode_attn_slice(vkv_pool* p, int32_t layer, int32_t slice, const void* q, const int32_t* table,
+                            int32_t max_blk, void* workspace, float scale, void* stream) {
+  int st = check_slice_args(p, layer, q, table, max_blk, workspace, "paged_decode_attn_slice");
+  if (st != VKV_OK) return st;
+  if (slice < 0 || slice >= (int32_t)p->slice_start.size() - 1) {
+    set_error("paged_decode_attn_slice: slice %d out of range [0,%d)", slice, (int)p->slice_start.size() - 1);
+    return VKV_E_INVAL;
+  }
+  return launch_slice(p, layer, slice, q, table, max_blk, workspace, scale, (hipStream_t)stream);
+}
+
+int kv_attn_finalize(vkv_pool* p, void* workspace, void* out, void* stream) {
+  int st = check_bound(p, workspace, "kv_attn_finalize");
+  if (st != VKV_OK) return st;
+  if (!out) { set_error("kv_attn_finalize: null output"); return VKV_E_INVAL; }
+  return launch_finalize(p, workspace, out, (hipStream_t)stream);
+}
+
+int kv_attn_check(vkv_pool* p, void* workspace, void* stream) {
+  int st = check_bound(p, workspace, "kv_attn_check");
+  if (st != VKV_OK) return st;
+  VKV_HIP(hipStreamSynchronize((hipStream_t)stream));
+  uint32_t flag = 0;
+  VKV_HIP(hipMemcpy(&flag, (char*)workspace + p->ws.header, 4, hipMemcpyDeviceToHost));
+  if (flag) { set_error("kv_attn_check: a slice met a block-table entry outside the pool"); return VKV_E_STATE; }
+  return VKV_OK;
+}
+
+int kv_attn_run_layer(vkv_pool* p, int32_t layer, int32_t* cursor, const void* q, const int32_t* table,
+                      int32_t max_blk, void* workspace, void* out, float scale, int32_t max_inflight,
+                      void* stream) {
+  int st = check_slice_args(p, layer, q, table, max_blk, workspace, "kv_attn_run_layer");
+  if (st != VKV_OK) return st;
+  const int32_t n_slices = (int32_t)p->slice_start.size() - 1;
+  if (!cursor || !out || *cursor < 0 || *cursor > n_slices || max_inflight < 1 || max_inflight > kMaxInflight) {
+    set_error("kv_attn_run_layer: bad cursor, output or max_inflight");
+    return VKV_E_INVAL;
+  }
+  hipStream_t hs = (hipStream_t)stream;
+  for (int i = 0; i < max_inflight; ++i)
+    if (!p->inflight_ev[i]) VKV_HIP(hipEventCreateWithFlags(&p->inflight_ev[i], hipEventDisableTiming));
+  int head = 0, count = 0;   // ring of events of enqueued, possibly unfinished slices
+  for (int32_t s = *cursor; s < n_slices; ++s) {
+    if (p->yield_flag.load(std::memory_order_acquire)) {
+      for (; count > 0; --count, head = (head + 1) % max_inflight) VKV_HIP(hipEventSynchronize(p->inflight_ev[head]));
+      *cursor = s;
+      return VKV_YIELDED;
+    }
+    if (count == max_inflight) {
+      VKV_HIP(hipEventSynchronize(p->inflight_ev[head]));
+      head = (head + 1) % max_inflight;
+      --count;
+    }
+    st = launch_slice(p, layer, s, q, table, max_blk, workspace, scale, hs);
+    if (st != VKV_OK) return st;
+    VKV_HIP(hipEventRecord(p->inflight_ev[(head + count) % max_inflight], hs));
+    ++count;
+  }
+  st = launch_finalize(p, workspace, out, hs);
+  if (st != VKV_OK) return st;
+  *cursor = n_slices;
+  return VKV_OK;
+}
+
+}  // extern "C"

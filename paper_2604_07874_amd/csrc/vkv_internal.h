@@ -1,0 +1,115 @@
+// Internal declarations shared by the translation units of libvalvekv.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <string>
+#include <utility>
+#include <vector>
+
+#include "valvekv.h"
+
+namespace vkv {
+
+void set_error(const char* fmt, ...);
+int  hip_fail(hipError_t e, const char* what);
+
+#define VKV_HIP(call)                                         \
+  do {                                                        \
+    hipError_t e_ = (call);                                   \
+    if (e_ != hipSuccess) return vkv::hip_fail(e_, #call);    \
+  } while (0)
+
+constexpr int kMaxInflight = 8;
+constexpr int kGroupTokens = 32;   // tokens one wave handles per loop iteration (two blocks)
+
+struct WorkItem {   // matches int4 on the device
+  int32_t seq, kv_head, first_block, n_tokens;
+};
+
+// Byte offsets of the pieces of the attention workspace.
+struct WorkspaceLayout {
+  uint64_t header = 0;       // 256 bytes; word 0 = bad-table-entry flag
+  uint64_t work = 0;         // WorkItem[n_items]
+  uint64_t seq_base = 0;     // int32[num_seqs + 1]: first item of each sequence
+  uint64_t part_ml = 0;      // float[n_items][G][2]: running max (log2 units), sum of exponentials
+  uint64_t part_acc = 0;     // float[n_items][G][D]: exp-weighted sum of V rows
+  uint64_t total = 0;
+  uint64_t upload_bytes = 0; // header + work + seq_base are written by kv_attn_bind
+};
+
+inline uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
+
+inline WorkspaceLayout workspace_layout(int64_t n_items, int64_t num_seqs, int G, int D) {
+  WorkspaceLayout w;
+  w.header = 0;
+  w.work = 256;
+  w.seq_base = w.work + (uint64_t)n_items * sizeof(WorkItem);
+  w.upload_bytes = w.seq_base + (uint64_t)(num_seqs + 1) * 4;
+  w.part_ml = align_up(w.upload_bytes, 256);
+  w.part_acc = align_up(w.part_ml + (uint64_t)n_items * G * 2 * 4, 256);
+  w.total = align_up(w.part_acc + (uint64_t)n_items * G * D * 4, 256);
+  return w;
+}
+
+}  // namespace vkv
+
+struct vkv_pool {
+  vkv_pool_config cfg{};
+  int G = 1;
+  uint64_t block_elems = 0;   // bf16 elements per block
+  uint64_t block_bytes = 0;
+
+  // occupancy
+  std::vector<uint8_t> live;
+  std::vector<std::pair<int32_t, int32_t>> released;   // handed-over ranges [lo,hi)
+  int64_t n_live = 0;
+
+  // attention plan (host)
+  bool has_plan = false;
+  uint64_t plan_gen = 0;
+  int32_t num_seqs = 0;
+  int32_t chunk_tokens = 0;
+  int32_t max_ctx_blocks = 0;                  // widest sequence in blocks
+  std::vector<vkv::WorkItem> work;
+  std::vector<int32_t> slice_start;
+  std::vector<int32_t> seq_base;
+  vkv::WorkspaceLayout ws{};
+
+  // binding of the plan to a device workspace
+  void* bound_ws = nullptr;
+  uint64_t bound_gen = 0;
+
+  // pinned staging (allocated on first device use)
+  void* stage = nullptr;
+  size_t stage_cap = 0;
+  hipEvent_t stage_ev = nullptr;
+  bool stage_inflight = false;
+  int32_t* remap_stage = nullptr;
+  size_t remap_stage_cap = 0;
+  hipEvent_t remap_ev = nullptr;
+  bool remap_inflight = false;
+  hipEvent_t grace_ev = nullptr;
+
+  // slice scheduler
+  hipEvent_t inflight_ev[vkv::kMaxInflight] = {};
+  std::atomic<int> yield_flag{0};
+
+  bool broken = false;   // a HIP call failed mid-operation
+};
+
+namespace vkv {
+
+bool in_released(const vkv_pool* p, int32_t b);
+int  ensure_stage(vkv_pool* p, size_t bytes);
+int  ensure_remap_stage(vkv_pool* p);
+
+// Host-side relocation plan; see kv_reclaim_plan.
+int plan_relocation(const vkv_pool* p, int32_t lo, int32_t hi,
+                    std::vector<int32_t>& src, std::vector<int32_t>& dst);
+
+}  // namespace vkv

@@ -18,5 +18,8 @@ from .workload import (  # noqa: F401
     pool_bits_for_blocks,
     fill_pool_torch,
     query_bits,
+    poison_unused_slots,
+    unused_slot_spans,
+    sample_ctx_len,
     BF16_NAN_BITS,
 )

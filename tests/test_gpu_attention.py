@@ -1,0 +1,68 @@
+"""GPU parity: paged decode attention through the C ABI against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle.attention import paged_decode_attention
+from oracle.plan import attention_plan
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-2   # max-abs bound on fp32 outputs (bf16 K/V, fp32 accumulate)
+
+
+@pytest.fixture(scope="module")
+def tiny_case():
+    from gpu_util import DeviceCase
+    c = DeviceCase(synth.workload("tiny"), seed=0)
+    yield c
+    c.close()
+
+
+def check_attention(c, layers, **plan_kw):
+    from gpu_util import layout_of
+    info = c.plan(**plan_kw)
+    worst = 0.0
+    for layer in layers:
+        q, q_t = c.q_dev(layer)
+        got = c.attention(layer, q_t)
+        ref = paged_decode_attention(c.pool_bits, layout_of(c.wl.geom), q, c.st.tables, c.st.ctx_len, layer)
+        assert np.isfinite(got).all()
+        err = float(np.max(np.abs(got.astype(np.float64) - ref)))
+        print(f"{c.wl.name} layer {layer}: items {info.n_items} slices {info.n_slices} max|err| {err:.3e}", flush=True)
+        worst = max(worst, err)
+    assert worst <= TOL
+    return worst
+
+
+def test_plan_matches_oracle(tiny_case):
+    c = tiny_case
+    g = c.wl.geom
+    for chunk, sb in [(64, 256 << 10), (32, 1), (256, 1 << 30), (128, 40000)]:
+        info = c.vkv.kv_attn_plan(c.pool, c.st.ctx_len, sb, chunk)
+        work, starts = c.vkv.kv_attn_plan_read(c.pool, info)
+        owork, ostarts = attention_plan(c.st.ctx_len, g.num_kv_heads, g.head_dim, g.block_tokens, chunk, sb)
+        assert np.array_equal(work, owork) and np.array_equal(starts, ostarts)
+        assert info.kv_bytes_per_layer == int(c.st.ctx_len.sum()) * g.kv_bytes_per_token_layer
+
+
+def test_tiny_attention(tiny_case):
+    check_attention(tiny_case, [0])
+
+
+@pytest.mark.parametrize("chunk,slice_bytes", [(32, 1), (64, 1 << 30), (96, 30000), (256, 100000)])
+def test_tiny_attention_any_partition(tiny_case, chunk, slice_bytes):
+    check_attention(tiny_case, [0], chunk_tokens=chunk, slice_bytes=slice_bytes)
+
+
+@pytest.mark.parametrize("name", ["llama8b_small", "llama70b_tp8_small", "offline_batch_small", "stress_small"])
+def test_small_configs(name):
+    from gpu_util import DeviceCase
+    wl = synth.workload(name)
+    c = DeviceCase(wl, seed=1)
+    try:
+        check_attention(c, range(wl.geom.num_layers))
+        check_attention(c, [wl.geom.num_layers - 1], chunk_tokens=128, slice_bytes=1 << 20)
+    finally:
+        c.close()

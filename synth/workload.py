@@ -138,17 +138,17 @@ WORKLOADS: Dict[str, Workload] = {
                        ("uniform", 256, 16384), 0.90, 26240),
     # Reduced shapes (same heads, fewer layers / sequences / blocks) that a CPU
     # oracle finishes in seconds yet span several chunks, slices and ragged tails.
-    "llama8b_small": Workload("llama8b_small", _g(2, 32, 8, 128, 1024, 32), 8,
-                              ("lognormal", 1024, 0.7, 16, 4096), 0.70, 256,
+    "llama8b_small": Workload("llama8b_small", _g(2, 32, 8, 128, 2048, 32), 8,
+                              ("lognormal", 1024, 0.7, 16, 4096), 0.70, 512,
                               chunk_bytes=8 << 20, slice_bytes=4 << 20),
-    "offline_batch_small": Workload("offline_batch_small", _g(2, 32, 8, 128, 1536, 64), 6,
-                                    ("uniform", 512, 6144), None, 256,
+    "offline_batch_small": Workload("offline_batch_small", _g(2, 32, 8, 128, 2560, 64), 6,
+                                    ("uniform", 512, 4096), None, 256,
                                     chunk_bytes=4 << 20, rate_cap=2e9, slice_bytes=4 << 20),
     "llama70b_tp8_small": Workload("llama70b_tp8_small", _g(3, 8, 1, 128, 4096, 64), 12,
                                    ("lognormal", 2048, 0.7, 16, 8192), 0.85, 512,
                                    chunk_bytes=2 << 20, slice_bytes=2 << 20),
-    "stress_small": Workload("stress_small", _g(2, 32, 8, 128, 1536, 64), 12,
-                             ("uniform", 256, 3072), 0.90, 128,
+    "stress_small": Workload("stress_small", _g(2, 32, 8, 128, 1536, 64), 10,
+                             ("uniform", 256, 2048), 0.90, 128,
                              chunk_bytes=4 << 20, slice_bytes=2 << 20),
 }
 

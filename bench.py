@@ -1,0 +1,333 @@
+#!/usr/bin/env python3
+"""Benchmark of the preemptible paged-KV decode + KV reclamation path on one MI355X.
+
+One step = one pass of the whole path over one synthetic batch:
+  plan (host) -> for every layer: attention slices through the slice scheduler + merge
+  -> reclaim the highest-address range (relocation plan, chunked block copy, table
+  rewrite, hand-over) -> the online tenant returns the range and the pool bookkeeping
+  is rewound so that every step does the same work (host-only, microseconds; the KV
+  bytes themselves never move back because the copy leaves the sources intact).
+
+Prints ONE JSON line.  `value` is the algorithmic HBM bytes of a step (K+V bytes read
+by attention in all layers + bytes read and written by the relocation) divided by the
+wall time of a step, inputs resident in HBM.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import threading
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published
+
+
+def percentile(a, q):
+    return float(np.percentile(np.asarray(a, dtype=np.float64), q)) if len(a) else None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="llama8b")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--chunk-tokens", type=int, default=None)
+    ap.add_argument("--slice-bytes", type=int, default=None)
+    ap.add_argument("--reclaim-chunk-bytes", type=int, default=None)
+    ap.add_argument("--max-inflight", type=int, default=2)
+    ap.add_argument("--yield-injections", type=int, default=1000)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-launch-events", action="store_true",
+                    help="do not bracket launches with timing events (roofline fields become null)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import synth
+    import paper_2604_07874_amd as vkv
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    wl = synth.workload(args.workload)
+    g = wl.geom
+    chunk_tokens = args.chunk_tokens or wl.chunk_tokens
+    slice_bytes = args.slice_bytes or wl.slice_bytes
+    rc_chunk = wl.chunk_bytes if args.reclaim_chunk_bytes is None else args.reclaim_chunk_bytes
+    L, S = g.num_layers, wl.num_seqs
+
+    # ---- inputs, resident in HBM before anything is timed --------------------------
+    t_setup = time.time()
+    st = synth.build_state(wl, args.seed, materialize_pool=False)
+    pool_t = torch.empty(g.pool_elems, dtype=torch.int16, device=dev)
+    synth.fill_pool_torch(pool_t, g, args.seed)
+    synth.poison_unused_slots(st, pool_t)
+    q_all = torch.stack([torch.from_numpy(synth.query_bits(wl, args.seed, l).view(np.int16)) for l in range(L)]).to(dev)
+    tables0 = torch.from_numpy(st.tables).to(dev)
+    tables = tables0.clone()
+    remap = torch.empty(g.num_blocks, dtype=torch.int32, device=dev)
+    out = torch.empty((L, S, g.num_q_heads, g.head_dim), dtype=torch.float32, device=dev)
+    pool = vkv.kv_pool_init(g.num_layers, g.num_q_heads, g.num_kv_heads, g.head_dim, g.num_blocks,
+                            g.blocks_per_handle, base=pool_t)
+    vkv.kv_pool_adopt(pool, np.flatnonzero(st.live).astype(np.int32))
+    info = vkv.kv_attn_plan(pool, st.ctx_len, slice_bytes, chunk_tokens)
+    ws = torch.empty(info.workspace_bytes, dtype=torch.uint8, device=dev)
+    lo, hi = wl.reclaim_range
+    remap_plan, plan_stats = vkv.kv_reclaim_plan(pool, lo, hi, g.num_blocks)
+    src_ids = np.flatnonzero(remap_plan != np.arange(g.num_blocks)).astype(np.int32)
+    dst_ids = remap_plan[src_ids].astype(np.int32)
+    torch.cuda.synchronize()
+    setup_s = time.time() - t_setup
+
+    stream = torch.cuda.current_stream()
+    launches_per_step = L * (info.n_slices + 1) + 2 + (len(src_ids) // max(1, rc_chunk // g.block_bytes) + 1 if rc_chunk else 1)
+    use_events = not args.no_launch_events
+    if use_events:
+        vkv.kv_profile_enable(pool, launches_per_step * (args.steps + 1) + 16)
+
+    def decode_pass():
+        for layer in range(L):
+            s_, cur = vkv.kv_attn_run_layer(pool, layer, 0, q_all[layer], tables, ws, out[layer],
+                                            max_inflight=args.max_inflight, stream=stream)
+            assert s_ == vkv.VKV_OK
+
+    def step():
+        vkv.kv_attn_plan(pool, st.ctx_len, slice_bytes, chunk_tokens)
+        vkv.kv_attn_bind(pool, ws, stream)
+        decode_pass()
+        rs = vkv.kv_reclaim_range(pool, lo, hi, tables, remap, chunk_bytes=rc_chunk, copy_stream=stream)
+        # the online tenant gives the range back; rewind the bookkeeping for the next step
+        vkv.kv_pool_return_range(pool, lo, hi)
+        vkv.kv_pool_free(pool, dst_ids)
+        vkv.kv_pool_adopt(pool, src_ids)
+        tables.copy_(tables0, non_blocking=True)
+        return rs
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    if use_events:
+        vkv.kv_profile_read(pool, 1 << 20)   # drop warm-up records
+
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        rs = step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    decode_bytes_layer = int(info.kv_bytes_per_layer)
+    decode_bytes = decode_bytes_layer * L
+    reclaim_traffic = 2 * int(rs.bytes_moved)
+    step_bytes = decode_bytes + reclaim_traffic
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # ---- per-kernel figures from the events recorded inside the timed region -------
+    roofline = None
+    roofline_reclaim = None
+    extra = {}
+    if use_events:
+        rec = vkv.kv_profile_read(pool, 1 << 20)
+        sl = rec[rec["kind"] == vkv.VKV_PROF_SLICE]
+        cb = rec[rec["kind"] == vkv.VKV_PROF_COMBINE]
+        rl = rec[rec["kind"] == vkv.VKV_PROF_RELOCATE]
+        rw = rec[rec["kind"] == vkv.VKV_PROF_REWRITE]
+        n_slice_launches = len(sl)
+        slice_ms_avg = float(sl["ms"].mean())
+        bytes_per_launch = decode_bytes_layer / info.n_slices
+        ach = bytes_per_launch / (slice_ms_avg * 1e-3) / 1e9
+        roofline = {"kernel": "paged_decode_attn_slice_kernel", "bound": "hbm", "achieved": round(ach, 1),
+                    "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4),
+                    "traffic": None, "avg_launch_us": round(slice_ms_avg * 1e3, 2),
+                    "bytes_per_launch": int(bytes_per_launch), "launches": int(n_slice_launches)}
+        if len(rl):
+            rl_ms = float(rl["ms"].sum()) / args.steps
+            rach = reclaim_traffic / (rl_ms * 1e-3) / 1e9
+            roofline_reclaim = {"kernel": "kv_block_relocate_kernel", "bound": "hbm", "achieved": round(rach, 1),
+                                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(rach / HBM_PEAK_GBPS, 4),
+                                "traffic": None, "avg_launch_us": round(float(rl["ms"].mean()) * 1e3, 2),
+                                "bytes_per_launch": int(reclaim_traffic / (len(rl) / args.steps)),
+                                "launches": int(len(rl))}
+        extra.update({
+            "slice_us_p50": round(percentile(sl["ms"], 50) * 1e3, 1),
+            "slice_us_p99": round(percentile(sl["ms"], 99) * 1e3, 1),
+            "slice_us_max": round(float(sl["ms"].max()) * 1e3, 1),
+            "combine_us_avg": round(float(cb["ms"].mean()) * 1e3, 2) if len(cb) else None,
+            "rewrite_us_avg": round(float(rw["ms"].mean()) * 1e3, 2) if len(rw) else None,
+        })
+        vkv.kv_profile_enable(pool, 0)
+
+    # ---- separate legs: decode only, reclaim only (wall clock, no launch events) ----
+    reps = max(3, args.steps)
+    decode_pass()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        decode_pass()
+    torch.cuda.synchronize()
+    decode_ms = (time.perf_counter() - t0) * 1e3 / reps
+    reclaim_ms = []
+    for _ in range(reps):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        vkv.kv_reclaim_range(pool, lo, hi, tables, remap, chunk_bytes=rc_chunk, copy_stream=stream)
+        reclaim_ms.append((time.perf_counter() - t0) * 1e3)
+        vkv.kv_pool_return_range(pool, lo, hi)
+        vkv.kv_pool_free(pool, dst_ids)
+        vkv.kv_pool_adopt(pool, src_ids)
+        tables.copy_(tables0)
+    reclaim_ms_med = float(np.median(reclaim_ms))
+    extra.update({
+        "decode_GBps": round(decode_bytes / (decode_ms * 1e-3) / 1e9, 1),
+        "decode_frac_of_peak": round(decode_bytes / (decode_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        "decode_ms_all_layers": round(decode_ms, 3),
+        "decode_tokens_per_s": round(S / (decode_ms * 1e-3), 1),
+        "reclaim_traffic_GBps": round(reclaim_traffic / (reclaim_ms_med * 1e-3) / 1e9, 1),
+        "reclaim_frac_of_peak": round(reclaim_traffic / (reclaim_ms_med * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        "reclaimed_GBps": round((hi - lo) * g.block_bytes / (reclaim_ms_med * 1e-3) / 1e9, 1),
+        "reclaim_ms": round(reclaim_ms_med, 3),
+        "reclaim_blocks_moved": int(rs.blocks_moved),
+    })
+
+    # ---- end-to-end yield latency: request at a random instant, until compute is off the GPU
+    if args.yield_injections > 0:
+        rng = np.random.default_rng(args.seed)
+        lat = []
+        req_t = [0.0]
+
+        def requester(delay):
+            time.sleep(delay)
+            req_t[0] = time.perf_counter()
+            vkv.kv_yield_request(pool)
+
+        n_inj = args.yield_injections
+        layer = 0
+        cur = 0
+        budget_s = 60.0
+        t_begin = time.time()
+        for i in range(n_inj):
+            if time.time() - t_begin > budget_s:
+                break
+            delay = float(rng.uniform(0.0, decode_ms * 1e-3))
+            th = threading.Thread(target=requester, args=(delay,))
+            th.start()
+            landed = None
+            while landed is None:
+                s_, cur = vkv.kv_attn_run_layer(pool, layer, cur, q_all[layer], tables, ws, out[layer],
+                                                max_inflight=args.max_inflight, stream=stream)
+                if s_ == vkv.VKV_YIELDED:
+                    landed = time.perf_counter()
+                else:
+                    layer = (layer + 1) % L
+                    cur = 0
+            th.join()
+            lat.append((landed - req_t[0]) * 1e6)
+            vkv.kv_yield_clear(pool)
+        torch.cuda.synchronize()
+        extra.update({"yield_latency_us_p50": round(percentile(lat, 50), 1),
+                      "yield_latency_us_p99": round(percentile(lat, 99), 1),
+                      "yield_latency_us_max": round(max(lat), 1), "yield_injections": len(lat)})
+
+    # ---- the CPU oracle on a bounded sample of the same workload --------------------
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        cpu_baseline = cpu_oracle_baseline(wl, st, pool_t, q_all, decode_bytes, reclaim_traffic)
+
+    vkv.kv_pool_destroy(pool)
+    line = {
+        "metric": "reclaim GB/s & paged-decode GB/s (% HBM peak); p99 yield latency us",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": (f"{wl.name}: L={L} Hq={g.num_q_heads} Hkv={g.num_kv_heads} D={g.head_dim} "
+                                f"block={g.block_tokens} batch={S} ctx={wl.ctx_dist} pool={g.pool_bytes / 2**30:.1f}GiB "
+                                f"occupancy={wl.occupancy} reclaim_top={(hi - lo) * g.block_bytes / 2**30:.2f}GiB"),
+                   "chunk_tokens": chunk_tokens, "slice_bytes": slice_bytes, "n_slices_per_layer": info.n_slices,
+                   "n_items_per_layer": info.n_items, "reclaim_chunk_bytes": rc_chunk,
+                   "max_inflight": args.max_inflight, "seed": args.seed},
+        "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
+        "step_bytes": step_bytes, "decode_bytes": decode_bytes, "reclaim_traffic_bytes": reclaim_traffic,
+        "setup_s": round(setup_s, 1),
+        "roofline": roofline, "roofline_reclaim": roofline_reclaim, "cpu_baseline": cpu_baseline,
+    }
+    line.update(extra)
+    print(json.dumps(line), flush=True)
+
+
+def cpu_oracle_baseline(wl, st, pool_t, q_all, decode_bytes, reclaim_traffic):
+    """Times the oracle (as it stands, one thread) on a sample and scales to one step's byte mix."""
+    import torch
+    from oracle.attention import PoolLayout, paged_decode_attention
+    from oracle.reclaim import ReclaimOracle
+    try:
+        from threadpoolctl import threadpool_limits
+    except Exception:   # pragma: no cover
+        threadpool_limits = None
+    g = wl.geom
+    layer = 0
+    n_seq = min(wl.num_seqs, 16)
+    # compact one-layer pool holding only the sampled sequences' blocks (ids renumbered; the
+    # attention result does not depend on block ids)
+    rows = st.tables[:n_seq]
+    ids = np.unique(rows[rows >= 0])
+    renum = np.full(g.num_blocks, -1, dtype=np.int32)
+    renum[ids] = np.arange(len(ids), dtype=np.int32)
+    layer_elems = 2 * g.num_kv_heads * g.block_tokens * g.head_dim
+    blocks = pool_t.view(g.num_blocks, g.block_elems)[torch.from_numpy(ids).to(pool_t.device).long(),
+                                                       layer * layer_elems:(layer + 1) * layer_elems]
+    sample_pool = blocks.cpu().numpy().view(np.uint16).reshape(-1)
+    sample_tables = np.where(rows >= 0, renum[np.maximum(rows, 0)], -1).astype(np.int32)
+    lay = PoolLayout(1, g.num_kv_heads, g.head_dim, g.block_tokens)
+    q = q_all[layer, :n_seq].cpu().numpy().view(np.uint16)
+    ctx = st.ctx_len[:n_seq]
+    import contextlib
+    with (threadpool_limits(limits=1) if threadpool_limits else contextlib.nullcontext()):
+        t0 = time.perf_counter()
+        paged_decode_attention(sample_pool, lay, q, sample_tables, ctx, 0)
+        t_attn = time.perf_counter() - t0
+        attn_bytes = int(ctx.sum()) * g.kv_bytes_per_token_layer
+        # reclamation: the top 512 blocks of the pool as a pool of their own, upper quarter reclaimed
+        nb_s = min(512, g.num_blocks) // g.blocks_per_handle * g.blocks_per_handle
+        base = g.num_blocks - nb_s
+        rc = max(g.blocks_per_handle, nb_s // 4 // g.blocks_per_handle * g.blocks_per_handle)
+        live = st.live[base:].copy()
+        if (live[:nb_s - rc] == 0).sum() < live[nb_s - rc:].sum():
+            live[:nb_s - rc] = 0            # crowded sample: make room, the copy cost is what is timed
+        pool_s = pool_t.view(g.num_blocks, g.block_elems)[base:].cpu().numpy().view(np.uint16)
+        tabs = np.flatnonzero(live).astype(np.int32).reshape(1, -1)
+        orc = ReclaimOracle(nb_s, g.blocks_per_handle, live, tabs, pool_s)
+        t0 = time.perf_counter()
+        status, src, dst, _ = orc.reclaim(nb_s - rc, nb_s)
+        t_rec = time.perf_counter() - t0
+        assert status == 0
+        rec_bytes = 2 * len(src) * g.block_bytes
+    attn_rate = attn_bytes / t_attn
+    rec_rate = rec_bytes / t_rec if t_rec > 0 and rec_bytes else float("inf")
+    step_s = decode_bytes / attn_rate + (reclaim_traffic / rec_rate if rec_bytes else 0.0)
+    return {"value": round((decode_bytes + reclaim_traffic) / step_s / 1e9, 4), "unit": "GB/s", "cores": 1,
+            "kind": "oracle",
+            "sample": (f"attention: layer 0 of the first {n_seq} sequences ({attn_bytes / 1e6:.0f} MB of K+V, "
+                       f"{t_attn:.1f} s); reclamation: top {nb_s} blocks as a pool, {len(src)} blocks moved "
+                       f"({rec_bytes / 1e6:.0f} MB read+written, {t_rec:.2f} s); scaled to one step's byte mix"),
+            "attention_GBps": round(attn_rate / 1e9, 4), "reclaim_GBps": round(rec_rate / 1e9, 3)}
+
+
+if __name__ == "__main__":
+    main()

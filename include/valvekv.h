@@ -166,15 +166,17 @@ int kv_attn_finalize(vkv_pool* pool, void* workspace, void* out_f32, void* strea
 int kv_attn_check(vkv_pool* pool, void* workspace, void* stream);
 
 /* Slice scheduler.  Issues slices *cursor_slice .. n_slices-1 of `layer`, then
- * the merge, keeping at most max_inflight (1..8) slices enqueued ahead of the
- * GPU so that the host stays close to the device.  Before each slice it tests
- * the yield flag; if set it stops issuing, waits until the slices already
+ * the merge, keeping at most max_inflight (1..8) launches unfinished so that the
+ * host stays close to the device; the count carries over from one call to the
+ * next (use one stream per pool for these calls).  Before each slice it tests
+ * the yield flag; if set it stops issuing, waits until the launches already
  * enqueued have finished, stores the next slice in *cursor_slice and returns
- * VKV_YIELDED: offline compute is then off the GPU.  A later call with the same
- * cursor continues without recomputing anything (the paper's requirement that
- * preempted work is resumed, not repeated: Section 2.2 on duplicated
- * iterations; Section 4.1).  On VKV_OK *cursor_slice = n_slices and the merge
- * has been enqueued (not waited for). */
+ * VKV_YIELDED: offline compute is then off the GPU, at most max_inflight
+ * launches after the request.  A later call with the same cursor continues
+ * without recomputing anything (the paper's requirement that preempted work is
+ * resumed, not repeated: Section 2.2 on duplicated iterations; Section 4.1).
+ * On VKV_OK *cursor_slice = n_slices and the merge has been enqueued (not
+ * waited for). */
 int kv_attn_run_layer(vkv_pool* pool, int32_t layer, int32_t* cursor_slice,
                       const void* q_bf16, const int32_t* block_table, int32_t max_blk,
                       void* workspace, void* out_f32, float softmax_scale,
@@ -239,6 +241,29 @@ int kv_reclaim_range(vkv_pool* pool, int32_t lo_block, int32_t hi_block,
  * changed). */
 int block_table_rewrite(int32_t* tables_dev, int64_t n_entries, const int32_t* remap_dev,
                         int32_t num_blocks, void* stream);
+
+/* ---- per-launch timing ---------------------------------------------------- */
+
+#define VKV_PROF_SLICE    0   /* paged_decode_attn_slice kernel; index = slice */
+#define VKV_PROF_COMBINE  1   /* merge kernel; index = 0 */
+#define VKV_PROF_RELOCATE 2   /* block copy launch; index = chunk number */
+#define VKV_PROF_REWRITE  3   /* table rewrite kernel */
+
+typedef struct vkv_profile_record {
+  int32_t kind;
+  int32_t index;
+  float   ms;                 /* device time between events recorded around the launch */
+} vkv_profile_record;
+
+/* With max_records > 0 every kernel launch of this pool is bracketed by two
+ * timing events on its stream until max_records launches have been recorded;
+ * 0 turns recording off and frees the events.  Used for roofline measurement;
+ * the events cost a few microseconds per launch. */
+int kv_profile_enable(vkv_pool* pool, int32_t max_records);
+
+/* Waits for the recorded launches to finish, writes up to cap records (launch
+ * order) to out_host, their count to *n_out, and restarts recording at zero. */
+int kv_profile_read(vkv_pool* pool, vkv_profile_record* out_host, int32_t cap, int32_t* n_out);
 
 #ifdef __cplusplus
 }

@@ -19,12 +19,14 @@ __all__ = [
     "kv_pool_return_range", "kv_pool_state", "kv_pool_check_tables", "kv_attn_plan", "kv_attn_plan_read",
     "kv_attn_bind", "paged_decode_attn_slice", "kv_attn_finalize", "kv_attn_check", "kv_attn_run_layer",
     "kv_yield_request", "kv_yield_clear", "kv_yield_pending", "kv_reclaim_plan", "kv_reclaim_range",
-    "block_table_rewrite",
+    "block_table_rewrite", "kv_profile_enable", "kv_profile_read", "ProfileRecord",
+    "VKV_PROF_SLICE", "VKV_PROF_COMBINE", "VKV_PROF_RELOCATE", "VKV_PROF_REWRITE",
 ]
 
 VKV_OK, VKV_YIELDED = 0, 1
 VKV_E_INVAL, VKV_E_NOSPACE, VKV_E_BUSY, VKV_E_HIP, VKV_E_STATE = -1, -2, -3, -4, -5
 VKV_RECLAIM_ASYNC = 1
+VKV_PROF_SLICE, VKV_PROF_COMBINE, VKV_PROF_RELOCATE, VKV_PROF_REWRITE = 0, 1, 2, 3
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
@@ -54,6 +56,10 @@ class AttnPlanInfo(C.Structure):
 class ReclaimStats(C.Structure):
     _fields_ = [("bytes_moved", C.c_uint64), ("blocks_moved", C.c_int32), ("blocks_in_range", C.c_int32),
                 ("n_chunks", C.c_int32), ("reserved", C.c_int32), ("host_seconds", C.c_double)]
+
+
+class ProfileRecord(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("index", C.c_int32), ("ms", C.c_float)]
 
 
 def _load():
@@ -92,6 +98,8 @@ _sigs = {
     "kv_reclaim_range": (C.c_int, [_P, C.c_int32, C.c_int32, _P, C.c_int64, C.c_uint64, C.c_uint64, _P, _P, _P,
                                    C.c_uint32, C.POINTER(ReclaimStats)]),
     "block_table_rewrite": (C.c_int, [_P, C.c_int64, _P, C.c_int32, _P]),
+    "kv_profile_enable": (C.c_int, [_P, C.c_int32]),
+    "kv_profile_read": (C.c_int, [_P, _P, C.c_int32, _I32P]),
 }
 for _name, (_res, _args) in _sigs.items():
     _fn = getattr(lib, _name)
@@ -262,3 +270,17 @@ def kv_reclaim_range(pool, lo: int, hi: int, block_tables, remap_dev, chunk_byte
 def block_table_rewrite(block_tables, remap_dev, num_blocks: int, stream=None):
     _check(lib.block_table_rewrite(_dev(block_tables), block_tables.numel(), _dev(remap_dev), num_blocks,
                                    _stream(stream)))
+
+
+# ---- per-launch timing ------------------------------------------------------------
+def kv_profile_enable(pool, max_records: int):
+    _check(lib.kv_profile_enable(pool, max_records))
+
+
+def kv_profile_read(pool, cap: int) -> np.ndarray:
+    """Structured array (kind, index, ms) of the launches recorded since the last read."""
+    dt = np.dtype([("kind", np.int32), ("index", np.int32), ("ms", np.float32)])
+    buf = np.zeros(cap, dtype=dt)
+    n = C.c_int32(0)
+    _check(lib.kv_profile_read(pool, buf.ctypes.data, cap, C.byref(n)))
+    return buf[:n.value]

@@ -316,6 +316,7 @@ static int launch_slice(vkv_pool* p, int32_t layer, int32_t slice, const void* q
   a.G = p->G;
   a.NB = p->cfg.num_blocks;
   a.scale_log2 = (scale != 0.f ? scale : 1.0f / std::sqrt((float)D)) * 1.4426950408889634f;
+  ProfScope prof(p, VKV_PROF_SLICE, slice, st);
   if (D == 128)
     hipLaunchKernelGGL(paged_decode_attn_slice_kernel<128>, dim3((unsigned)count), dim3(256), 0, st, a);
   else
@@ -340,6 +341,7 @@ static int check_slice_args(vkv_pool* p, int32_t layer, const void* q, const int
 
 static int launch_finalize(vkv_pool* p, void* workspace, void* out, hipStream_t st) {
   char* ws = (char*)workspace;
+  ProfScope prof(p, VKV_PROF_COMBINE, 0, st);
   hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)(p->num_seqs * p->cfg.num_kv_heads)), dim3(256), 0, st,
                      (const float*)(ws + p->ws.part_acc), (const float*)(ws + p->ws.part_ml),
                      (const int32_t*)(ws + p->ws.seq_base), (float*)out, p->cfg.num_kv_heads, p->G, p->cfg.head_dim);
@@ -487,25 +489,45 @@ int kv_attn_run_layer(vkv_pool* p, int32_t layer, int32_t* cursor, const void* q
   hipStream_t hs = (hipStream_t)stream;
   for (int i = 0; i < max_inflight; ++i)
     if (!p->inflight_ev[i]) VKV_HIP(hipEventCreateWithFlags(&p->inflight_ev[i], hipEventDisableTiming));
-  int head = 0, count = 0;   // ring of events of enqueued, possibly unfinished slices
+  auto drain = [&]() -> int {
+    for (; p->inflight_count > 0; --p->inflight_count, p->inflight_head = (p->inflight_head + 1) % p->inflight_cap)
+      VKV_HIP(hipEventSynchronize(p->inflight_ev[p->inflight_head]));
+    p->inflight_head = 0;
+    return VKV_OK;
+  };
+  if (p->inflight_cap != max_inflight) {
+    st = drain();
+    if (st != VKV_OK) return st;
+    p->inflight_cap = max_inflight;
+  }
+  // one more launch may be enqueued once fewer than max_inflight are unfinished
+  auto admit = [&]() -> int {
+    if (p->inflight_count == max_inflight) {
+      VKV_HIP(hipEventSynchronize(p->inflight_ev[p->inflight_head]));
+      p->inflight_head = (p->inflight_head + 1) % max_inflight;
+      --p->inflight_count;
+    }
+    return VKV_OK;
+  };
+  auto track = [&]() -> int {
+    VKV_HIP(hipEventRecord(p->inflight_ev[(p->inflight_head + p->inflight_count) % max_inflight], hs));
+    ++p->inflight_count;
+    return VKV_OK;
+  };
   for (int32_t s = *cursor; s < n_slices; ++s) {
     if (p->yield_flag.load(std::memory_order_acquire)) {
-      for (; count > 0; --count, head = (head + 1) % max_inflight) VKV_HIP(hipEventSynchronize(p->inflight_ev[head]));
+      st = drain();
+      if (st != VKV_OK) return st;
       *cursor = s;
       return VKV_YIELDED;
     }
-    if (count == max_inflight) {
-      VKV_HIP(hipEventSynchronize(p->inflight_ev[head]));
-      head = (head + 1) % max_inflight;
-      --count;
-    }
-    st = launch_slice(p, layer, s, q, table, max_blk, workspace, scale, hs);
-    if (st != VKV_OK) return st;
-    VKV_HIP(hipEventRecord(p->inflight_ev[(head + count) % max_inflight], hs));
-    ++count;
+    if ((st = admit()) != VKV_OK) return st;
+    if ((st = launch_slice(p, layer, s, q, table, max_blk, workspace, scale, hs)) != VKV_OK) return st;
+    if ((st = track()) != VKV_OK) return st;
   }
-  st = launch_finalize(p, workspace, out, hs);
-  if (st != VKV_OK) return st;
+  if ((st = admit()) != VKV_OK) return st;
+  if ((st = launch_finalize(p, workspace, out, hs)) != VKV_OK) return st;
+  if ((st = track()) != VKV_OK) return st;
   *cursor = n_slices;
   return VKV_OK;
 }

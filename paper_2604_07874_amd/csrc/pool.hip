@@ -122,6 +122,7 @@ int kv_pool_destroy(vkv_pool* p) {
   if (p->grace_ev) (void)hipEventDestroy(p->grace_ev);
   for (auto& e : p->inflight_ev)
     if (e) (void)hipEventDestroy(e);
+  for (auto& e : p->prof_ev) (void)hipEventDestroy(e);
   delete p;
   return VKV_OK;
 }
@@ -218,6 +219,39 @@ int kv_pool_check_tables(vkv_pool* p, const int32_t* t, int64_t n) {
       return VKV_E_STATE;
     }
   }
+  return VKV_OK;
+}
+
+int kv_profile_enable(vkv_pool* p, int32_t max_records) {
+  if (!p || max_records < 0 || max_records > (1 << 20)) { set_error("kv_profile_enable: bad argument"); return VKV_E_INVAL; }
+  for (auto& e : p->prof_ev) (void)hipEventDestroy(e);
+  p->prof_ev.clear();
+  p->prof_tag.clear();
+  p->prof_cap = 0;
+  p->prof_ev.reserve((size_t)max_records * 2);
+  for (int32_t i = 0; i < 2 * max_records; ++i) {
+    hipEvent_t e = nullptr;
+    VKV_HIP(hipEventCreate(&e));
+    p->prof_ev.push_back(e);
+  }
+  p->prof_cap = max_records;
+  return VKV_OK;
+}
+
+int kv_profile_read(vkv_pool* p, vkv_profile_record* out, int32_t cap, int32_t* n_out) {
+  if (!p || cap < 0 || (cap > 0 && !out) || !n_out) { set_error("kv_profile_read: bad argument"); return VKV_E_INVAL; }
+  const int32_t n = std::min<int32_t>(cap, (int32_t)p->prof_tag.size());
+  for (int32_t i = 0; i < n; ++i) {
+    VKV_HIP(hipEventSynchronize(p->prof_ev[2 * i + 1]));
+    float ms = 0.f;
+    VKV_HIP(hipEventElapsedTime(&ms, p->prof_ev[2 * i], p->prof_ev[2 * i + 1]));
+    out[i].kind = p->prof_tag[i].first;
+    out[i].index = p->prof_tag[i].second;
+    out[i].ms = ms;
+  }
+  if (!p->prof_tag.empty()) VKV_HIP(hipEventSynchronize(p->prof_ev[2 * p->prof_tag.size() - 1]));
+  *n_out = n;
+  p->prof_tag.clear();
   return VKV_OK;
 }
 

@@ -97,8 +97,11 @@ int plan_relocation(const vkv_pool* p, int32_t lo, int32_t hi, std::vector<int32
   return VKV_OK;
 }
 
-static int launch_rewrite(int32_t* tables, int64_t n, const int32_t* remap, int32_t nb, hipStream_t st) {
+static int launch_rewrite(vkv_pool* p, int32_t* tables, int64_t n, const int32_t* remap, int32_t nb,
+                          hipStream_t st) {
   if (n == 0) return VKV_OK;
+  vkv_pool none;
+  ProfScope prof(p ? p : &none, VKV_PROF_REWRITE, 0, st);
   int64_t blocks = std::min<int64_t>((n + 255) / 256, 2048);
   hipLaunchKernelGGL(block_table_rewrite_kernel, dim3((unsigned)blocks), dim3(256), 0, st, tables, n, remap, nb);
   VKV_HIP(hipGetLastError());
@@ -179,6 +182,7 @@ int kv_reclaim_range(vkv_pool* p, int32_t lo, int32_t hi, int32_t* tables, int64
       std::this_thread::sleep_until(due);
     }
     const int32_t first = src[i], last = src[j - 1];
+    ProfScope prof(p, VKV_PROF_RELOCATE, n_chunks, cs);
     hipLaunchKernelGGL(kv_block_relocate_kernel, dim3((unsigned)(last - first + 1), pieces), dim3(kCopyThreads), 0,
                        cs, (u32x4*)p->cfg.base, (const int32_t*)remap_dev, first, block_vecs);
     he = hipGetLastError();
@@ -186,7 +190,7 @@ int kv_reclaim_range(vkv_pool* p, int32_t lo, int32_t hi, int32_t* tables, int64
     sent += (uint64_t)(j - i) * p->block_bytes;
     ++n_chunks;
   }
-  if (launch_rewrite(tables, n_entries, remap_dev, nb, cs) != VKV_OK) return fail(VKV_E_HIP);
+  if (launch_rewrite(p, tables, n_entries, remap_dev, nb, cs) != VKV_OK) return fail(VKV_E_HIP);
 
   if (!(flags & VKV_RECLAIM_ASYNC)) {
     he = hipStreamSynchronize(cs);
@@ -223,7 +227,7 @@ int block_table_rewrite(int32_t* tables, int64_t n_entries, const int32_t* remap
     set_error("block_table_rewrite: bad argument");
     return VKV_E_INVAL;
   }
-  return launch_rewrite(tables, n_entries, remap_dev, num_blocks, (hipStream_t)stream);
+  return launch_rewrite(nullptr, tables, n_entries, remap_dev, num_blocks, (hipStream_t)stream);
 }
 
 }  // extern "C"

@@ -96,8 +96,16 @@ struct vkv_pool {
   hipEvent_t grace_ev = nullptr;
 
   // slice scheduler
+  // ring of events behind launches that may still be running; it persists across
+  // kv_attn_run_layer calls so the host never runs more than max_inflight launches ahead
   hipEvent_t inflight_ev[vkv::kMaxInflight] = {};
+  int inflight_head = 0, inflight_count = 0, inflight_cap = 0;
   std::atomic<int> yield_flag{0};
+
+  // per-launch timing (kv_profile_enable)
+  std::vector<hipEvent_t> prof_ev;      // 2 per record: start, end
+  std::vector<std::pair<int32_t, int32_t>> prof_tag;   // (kind, index)
+  int32_t prof_cap = 0;
 
   bool broken = false;   // a HIP call failed mid-operation
 };
@@ -107,6 +115,23 @@ namespace vkv {
 bool in_released(const vkv_pool* p, int32_t b);
 int  ensure_stage(vkv_pool* p, size_t bytes);
 int  ensure_remap_stage(vkv_pool* p);
+
+// Brackets one kernel launch with timing events while recording is on.
+struct ProfScope {
+  vkv_pool* p;
+  hipStream_t st;
+  int slot = -1;
+  ProfScope(vkv_pool* pool, int32_t kind, int32_t index, hipStream_t stream) : p(pool), st(stream) {
+    if (p->prof_cap > 0 && (int32_t)p->prof_tag.size() < p->prof_cap) {
+      slot = (int)p->prof_tag.size();
+      p->prof_tag.emplace_back(kind, index);
+      (void)hipEventRecord(p->prof_ev[2 * slot], st);
+    }
+  }
+  ~ProfScope() {
+    if (slot >= 0) (void)hipEventRecord(p->prof_ev[2 * slot + 1], st);
+  }
+};
 
 // Host-side relocation plan; see kv_reclaim_plan.
 int plan_relocation(const vkv_pool* p, int32_t lo, int32_t hi,

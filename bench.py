@@ -96,7 +96,7 @@ def main():
     setup_s = time.time() - t_setup
 
     stream = torch.cuda.current_stream()
-    launches_per_step = L * (info.n_slices + 1) + 2 + (len(src_ids) // max(1, rc_chunk // g.block_bytes) + 1 if rc_chunk else 1)
+    launches_per_step = L * info.n_slices + 2 + (len(src_ids) // max(1, rc_chunk // g.block_bytes) + 1 if rc_chunk else 1)
     use_events = not args.no_launch_events
     if use_events:
         vkv.kv_profile_enable(pool, launches_per_step * (args.steps + 1) + 16)
@@ -146,7 +146,6 @@ def main():
     if use_events:
         rec = vkv.kv_profile_read(pool, 1 << 20)
         sl = rec[rec["kind"] == vkv.VKV_PROF_SLICE]
-        cb = rec[rec["kind"] == vkv.VKV_PROF_COMBINE]
         rl = rec[rec["kind"] == vkv.VKV_PROF_RELOCATE]
         rw = rec[rec["kind"] == vkv.VKV_PROF_REWRITE]
         n_slice_launches = len(sl)
@@ -169,7 +168,6 @@ def main():
             "slice_us_p50": round(percentile(sl["ms"], 50) * 1e3, 1),
             "slice_us_p99": round(percentile(sl["ms"], 99) * 1e3, 1),
             "slice_us_max": round(float(sl["ms"].max()) * 1e3, 1),
-            "combine_us_avg": round(float(cb["ms"].mean()) * 1e3, 2) if len(cb) else None,
             "rewrite_us_avg": round(float(rw["ms"].mean()) * 1e3, 2) if len(rw) else None,
         })
         vkv.kv_profile_enable(pool, 0)

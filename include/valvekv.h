@@ -123,7 +123,7 @@ typedef struct vkv_attn_plan_info {
  * one item each), so that a yield request is honoured within one slice
  * (Section 2.3, Challenge 1: bounded preemption latency).
  * ctx_len_host[s] >= 1 counts the tokens already in the cache, the newest
- * included.  chunk_tokens: positive multiple of 32.  Replaces any earlier plan.
+ * included.  chunk_tokens: multiple of 32 in [32, 2048].  Replaces any earlier plan.
  * Errors: VKV_E_INVAL. */
 int kv_attn_plan(vkv_pool* pool, const int32_t* ctx_len_host, int32_t num_seqs,
                  uint64_t slice_bytes, int32_t chunk_tokens, vkv_attn_plan_info* info_out);
@@ -133,40 +133,42 @@ int kv_attn_plan(vkv_pool* pool, const int32_t* ctx_len_host, int32_t num_seqs,
 int kv_attn_plan_read(vkv_pool* pool, int32_t* work_out_host, int32_t* slice_start_out_host);
 
 /* Enqueues the upload of the current plan into `workspace` (device,
- * >= workspace_bytes, 256-byte aligned) on `stream`.  The workspace also holds
- * the per-item partial results of one layer at a time; it is the resume state
- * after a yield and must not be touched by the caller between slices of a layer.
- * Blocks the host only if an earlier upload from the same pool is still in
- * flight.  Errors: VKV_E_INVAL, VKV_E_STATE (no plan), VKV_E_HIP. */
+ * >= workspace_bytes, 256-byte aligned) on `stream` and zeroes its progress
+ * counters.  The workspace also holds the per-item partial results and the
+ * per-(sequence, kv head) progress counters of the layer in flight; it is the
+ * resume state after a yield and must not be touched by the caller between
+ * slices of a layer.  A layer that was started must be finished (all its
+ * slices run) before another layer uses the workspace; to abandon a layer,
+ * bind again.  Blocks the host only if an earlier upload from the same pool is
+ * still in flight.  Errors: VKV_E_INVAL, VKV_E_STATE (no plan), VKV_E_HIP. */
 int kv_attn_bind(vkv_pool* pool, void* workspace, uint64_t workspace_bytes, void* stream);
 
 /* Enqueues one slice of one layer: for every work item of the slice, scores
  * q.k/sqrt(D) (or * softmax_scale if nonzero) of the G query heads of the
  * item's kv head against the item's tokens, running maximum, sum of
- * exponentials and exp-weighted sum of V rows, written to the workspace.
- * Query head g uses kv head g / G.  Token t of a sequence lives in block
- * block_table[seq][t / 16], slot t % 16; slots past the sequence length are
- * never read.  bf16 inputs, fp32 accumulation.
+ * exponentials and exp-weighted sum of V rows.  The item that completes a
+ * (sequence, kv head) pair merges the pair's chunks (log-sum-exp merge, in chunk
+ * order) and writes out[seq][head][:], so `out` is complete once every slice of
+ * the layer has run; slices of a layer may run in any order and any number of
+ * launches apart.  Query head g uses kv head g / G.  Token t of a sequence lives
+ * in block block_table[seq][t / 16], slot t % 16; slots past the sequence length
+ * are never read.  bf16 inputs, fp32 accumulation.
  *   q_bf16       device [num_seqs][num_q_heads][head_dim] for this layer
  *   block_table  device int32 [>= num_seqs rows][max_blk], -1 padded
+ *   out_f32      device fp32 [num_seqs][num_q_heads][head_dim]
  * The host checks layer, slice and max_blk against the plan (VKV_E_INVAL,
  * VKV_E_STATE); the kernel skips table entries outside [0, NB) and raises a flag
- * that kv_attn_finalize's status word reports. */
+ * that kv_attn_check reports. */
 int paged_decode_attn_slice(vkv_pool* pool, int32_t layer, int32_t slice,
                             const void* q_bf16, const int32_t* block_table, int32_t max_blk,
-                            void* workspace, float softmax_scale, void* stream);
-
-/* Enqueues the merge of the layer's partial results:
- * out fp32 device [num_seqs][num_q_heads][head_dim].  Call after all slices of
- * the layer have been enqueued on the same stream. */
-int kv_attn_finalize(vkv_pool* pool, void* workspace, void* out_f32, void* stream);
+                            void* workspace, void* out_f32, float softmax_scale, void* stream);
 
 /* Waits for `stream` and returns VKV_E_STATE if any slice since the last bind
  * met a block-table entry outside [0, NB); VKV_OK otherwise. */
 int kv_attn_check(vkv_pool* pool, void* workspace, void* stream);
 
-/* Slice scheduler.  Issues slices *cursor_slice .. n_slices-1 of `layer`, then
- * the merge, keeping at most max_inflight (1..8) launches unfinished so that the
+/* Slice scheduler.  Issues slices *cursor_slice .. n_slices-1 of `layer`,
+ * keeping at most max_inflight (1..8) launches unfinished so that the
  * host stays close to the device; the count carries over from one call to the
  * next (use one stream per pool for these calls).  Before each slice it tests
  * the yield flag; if set it stops issuing, waits until the launches already
@@ -175,7 +177,7 @@ int kv_attn_check(vkv_pool* pool, void* workspace, void* stream);
  * launches after the request.  A later call with the same cursor continues
  * without recomputing anything (the paper's requirement that preempted work is
  * resumed, not repeated: Section 2.2 on duplicated iterations; Section 4.1).
- * On VKV_OK *cursor_slice = n_slices and the merge has been enqueued (not
+ * On VKV_OK *cursor_slice = n_slices and every slice has been enqueued (not
  * waited for). */
 int kv_attn_run_layer(vkv_pool* pool, int32_t layer, int32_t* cursor_slice,
                       const void* q_bf16, const int32_t* block_table, int32_t max_blk,
@@ -245,9 +247,8 @@ int block_table_rewrite(int32_t* tables_dev, int64_t n_entries, const int32_t* r
 /* ---- per-launch timing ---------------------------------------------------- */
 
 #define VKV_PROF_SLICE    0   /* paged_decode_attn_slice kernel; index = slice */
-#define VKV_PROF_COMBINE  1   /* merge kernel; index = 0 */
-#define VKV_PROF_RELOCATE 2   /* block copy launch; index = chunk number */
-#define VKV_PROF_REWRITE  3   /* table rewrite kernel */
+#define VKV_PROF_RELOCATE 1   /* block copy launch; index = chunk number */
+#define VKV_PROF_REWRITE  2   /* table rewrite kernel */
 
 typedef struct vkv_profile_record {
   int32_t kind;

@@ -17,16 +17,16 @@ __all__ = [
     "VKV_RECLAIM_ASYNC", "VkvError", "PoolConfig", "AttnPlanInfo", "ReclaimStats", "lib", "library_path",
     "last_error", "kv_pool_init", "kv_pool_destroy", "kv_pool_alloc", "kv_pool_adopt", "kv_pool_free",
     "kv_pool_return_range", "kv_pool_state", "kv_pool_check_tables", "kv_attn_plan", "kv_attn_plan_read",
-    "kv_attn_bind", "paged_decode_attn_slice", "kv_attn_finalize", "kv_attn_check", "kv_attn_run_layer",
+    "kv_attn_bind", "paged_decode_attn_slice", "kv_attn_check", "kv_attn_run_layer",
     "kv_yield_request", "kv_yield_clear", "kv_yield_pending", "kv_reclaim_plan", "kv_reclaim_range",
     "block_table_rewrite", "kv_profile_enable", "kv_profile_read", "ProfileRecord",
-    "VKV_PROF_SLICE", "VKV_PROF_COMBINE", "VKV_PROF_RELOCATE", "VKV_PROF_REWRITE",
+    "VKV_PROF_SLICE", "VKV_PROF_RELOCATE", "VKV_PROF_REWRITE",
 ]
 
 VKV_OK, VKV_YIELDED = 0, 1
 VKV_E_INVAL, VKV_E_NOSPACE, VKV_E_BUSY, VKV_E_HIP, VKV_E_STATE = -1, -2, -3, -4, -5
 VKV_RECLAIM_ASYNC = 1
-VKV_PROF_SLICE, VKV_PROF_COMBINE, VKV_PROF_RELOCATE, VKV_PROF_REWRITE = 0, 1, 2, 3
+VKV_PROF_SLICE, VKV_PROF_RELOCATE, VKV_PROF_REWRITE = 0, 1, 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
@@ -87,8 +87,7 @@ _sigs = {
     "kv_attn_plan": (C.c_int, [_P, _P, C.c_int32, C.c_uint64, C.c_int32, C.POINTER(AttnPlanInfo)]),
     "kv_attn_plan_read": (C.c_int, [_P, _P, _P]),
     "kv_attn_bind": (C.c_int, [_P, _P, C.c_uint64, _P]),
-    "paged_decode_attn_slice": (C.c_int, [_P, C.c_int32, C.c_int32, _P, _P, C.c_int32, _P, C.c_float, _P]),
-    "kv_attn_finalize": (C.c_int, [_P, _P, _P, _P]),
+    "paged_decode_attn_slice": (C.c_int, [_P, C.c_int32, C.c_int32, _P, _P, C.c_int32, _P, _P, C.c_float, _P]),
     "kv_attn_check": (C.c_int, [_P, _P, _P]),
     "kv_attn_run_layer": (C.c_int, [_P, C.c_int32, _I32P, _P, _P, C.c_int32, _P, _P, C.c_float, C.c_int32, _P]),
     "kv_yield_request": (C.c_int, [_P]),
@@ -211,14 +210,10 @@ def kv_attn_bind(pool, workspace, stream=None):
     _check(lib.kv_attn_bind(pool, _dev(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
-def paged_decode_attn_slice(pool, layer: int, slice_idx: int, q, block_table, workspace,
+def paged_decode_attn_slice(pool, layer: int, slice_idx: int, q, block_table, workspace, out,
                             softmax_scale: float = 0.0, stream=None):
     _check(lib.paged_decode_attn_slice(pool, layer, slice_idx, _dev(q), _dev(block_table), block_table.shape[-1],
-                                       _dev(workspace), softmax_scale, _stream(stream)))
-
-
-def kv_attn_finalize(pool, workspace, out, stream=None):
-    _check(lib.kv_attn_finalize(pool, _dev(workspace), _dev(out), _stream(stream)))
+                                       _dev(workspace), _dev(out), softmax_scale, _stream(stream)))
 
 
 def kv_attn_check(pool, workspace, stream=None):

@@ -22,6 +22,14 @@
 //   Softmax statistics are per lane (= per query head): running max m (log2 units), sum l,
 //   and the accumulator is rescaled when m grows.  l is summed from the bf16-rounded
 //   weights that enter the MFMA, so the result is an exact convex combination of V rows.
+//   The block ids of the item sit in two VGPRs (one table entry per lane) and are read
+//   with v_readlane, so no load sits between two groups' K/V fetches.
+//   Merge: an item that covers its whole sequence writes the output directly.  Otherwise
+//   it writes (max, sum, weighted V sum) to the workspace and bumps a per-(sequence, kv
+//   head) counter; the workgroup that brings the counter to the chunk count merges all
+//   chunks in chunk order (so the bits do not depend on which one arrives last), writes
+//   the output and zeroes the counter.  The counters live in the workspace, so this
+//   works across slices and across a yield.
 #include "vkv_internal.h"
 
 #include <algorithm>
@@ -42,18 +50,29 @@ struct AttnParams {
   const int32_t* table;      // [rows][max_blk]
   float* part_acc;           // [n_items][G][D]
   float* part_ml;            // [n_items][G][2]
+  const int32_t* seq_base;   // [S+1] first item of each sequence
+  int32_t* done;             // [S][Hkv] chunks finished in the current layer
+  float* out;                // [S][Hq][D]
   uint32_t* err;             // workspace header word 0
   uint64_t block_elems;
   uint32_t v_off;            // elements from a block's K plane to its V plane (one layer)
   int32_t item_first;
   int32_t max_blk;
-  int32_t Hq, G, NB;
+  int32_t Hq, Hkv, G, NB;
   float scale_log2;          // softmax scale * log2(e)
 };
 
 template <int D> struct LdVec;
 template <> struct LdVec<128> { using type = u32x4; };
 template <> struct LdVec<64> { using type = u32x2; };
+
+// device-scope relaxed atomic accesses: coherent across the whole GPU without cache maintenance
+__device__ __forceinline__ void st_dev(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_dev(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
 // word j of a lane-row register as 32 bits (two bf16)
 __device__ __forceinline__ uint32_t word_of(const u32x4& v, int j) { return v[j]; }
@@ -97,6 +116,11 @@ __global__ __launch_bounds__(256, 2) void paged_decode_attn_slice_kernel(const A
   const uint16_t* kplane = p.pool + (size_t)it.kv_head * (16 * D);
   unsigned char* tile = lds + wave * TILE;
 
+  // block ids of this item: lane j holds entries j and 64+j (chunk_tokens <= 2048)
+  const int nblk_item = (ntok + 15) >> 4;
+  const int32_t tb0 = lane < nblk_item ? trow[lane] : -1;
+  const int32_t tb1 = 64 + lane < nblk_item ? trow[64 + lane] : -1;
+
   f32x4 acc[EPL];
 #pragma unroll
   for (int dt = 0; dt < EPL; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -108,9 +132,8 @@ __global__ __launch_bounds__(256, 2) void paged_decode_attn_slice_kernel(const A
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
       const int bi = grp * 2 + b;
-      const bool have = bi * 16 < ntok;
-      int32_t blk = have ? trow[bi] : -1;
-      blk = __builtin_amdgcn_readfirstlane(blk);
+      const bool have = bi < nblk_item;
+      const int32_t blk = bi < 64 ? __builtin_amdgcn_readlane(tb0, bi & 63) : __builtin_amdgcn_readlane(tb1, bi & 63);
       if (blk < 0 || blk >= p.NB) {
         if (have && lane == 0) atomicOr(p.err, 1u);
 #pragma unroll
@@ -238,6 +261,9 @@ __global__ __launch_bounds__(256, 2) void paged_decode_attn_slice_kernel(const A
   }
   __syncthreads();
   const size_t item = (size_t)p.item_first + blockIdx.x;
+  const int base = p.seq_base[it.seq];
+  const int nch = (p.seq_base[it.seq + 1] - base) / p.Hkv;   // chunks of this sequence
+  float* orow = p.out + ((size_t)it.seq * p.Hq + (size_t)it.kv_head * G) * D;
   for (int e = threadIdx.x; e < G * D; e += 256) {
     const int g = e / D, d = e - g * D;
     float M = sm_m[0][g];
@@ -250,35 +276,69 @@ __global__ __launch_bounds__(256, 2) void paged_decode_attn_slice_kernel(const A
       num += wt * macc[((size_t)w * G + g) * D + d];
       den += wt * sm_l[w][g];
     }
-    p.part_acc[(item * G + g) * D + d] = num;
-    if (d == 0) {
-      p.part_ml[(item * G + g) * 2 + 0] = M;
-      p.part_ml[(item * G + g) * 2 + 1] = den;
+    if (nch == 1) {
+      orow[e] = num / den;
+    } else {
+      st_dev(&p.part_acc[(item * G + g) * D + d], num);
+      if (d == 0) {
+        st_dev(&p.part_ml[(item * G + g) * 2 + 0], M);
+        st_dev(&p.part_ml[(item * G + g) * 2 + 1], den);
+      }
     }
   }
-}
+  if (nch == 1) return;
 
-// out[s][h*G+g][:] = sum_c 2^(m_c - M) acc_c / sum_c 2^(m_c - M) l_c over the chunks c of (s, h).
-__global__ __launch_bounds__(256) void attn_combine_kernel(const float* __restrict__ part_acc,
-                                                           const float* __restrict__ part_ml,
-                                                           const int32_t* __restrict__ seq_base, float* __restrict__ out,
-                                                           int Hkv, int G, int D) {
-  const int s = blockIdx.x / Hkv, h = blockIdx.x - s * Hkv;
-  const int base = seq_base[s];
-  const int nch = (seq_base[s + 1] - base) / Hkv;
+  // Publish the partial result, then count this chunk as done.  The partial results and the
+  // counter are only ever touched with device-scope atomic accesses, which are performed at
+  // the device's coherence point (not in the per-XCD L2), so no cache write-back or
+  // invalidation is needed: each wave waits until its stores are acknowledged, the barrier
+  // collects the waves, then thread 0 bumps the counter.
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __syncthreads();
+  __shared__ int sm_last;
+  int32_t* done = p.done + (size_t)it.seq * p.Hkv + it.kv_head;
+  if (threadIdx.x == 0)
+    sm_last = __hip_atomic_fetch_add(done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == nch - 1;
+  __syncthreads();
+  if (!sm_last) return;
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+
+  // Last chunk of this (sequence, kv head): merge all chunks, in chunk order.
+  // Stage every chunk's (max, sum) in LDS first so the loads below are independent.
+  float* cm = reinterpret_cast<float*>(lds);       // [nch][G]
+  float* cl = cm + (size_t)nch * G;                 // [nch][G]
+  for (int i = threadIdx.x; i < nch * G; i += 256) {
+    const int c = i / G, g = i - c * G;
+    const size_t ig = ((size_t)base + (size_t)c * p.Hkv + it.kv_head) * G + g;
+    cm[i] = ld_dev(&p.part_ml[ig * 2]);
+    cl[i] = ld_dev(&p.part_ml[ig * 2 + 1]);
+  }
+  __syncthreads();
   for (int e = threadIdx.x; e < G * D; e += 256) {
     const int g = e / D, d = e - g * D;
-    float M = -INFINITY;
-    for (int c = 0; c < nch; ++c) M = fmaxf(M, part_ml[(((size_t)base + (size_t)c * Hkv + h) * G + g) * 2]);
+    float M = NEG_INF;
+    for (int c = 0; c < nch; ++c) M = fmaxf(M, cm[c * G + g]);
     float num = 0.f, den = 0.f;
-    for (int c = 0; c < nch; ++c) {
-      const size_t ig = ((size_t)base + (size_t)c * Hkv + h) * G + g;
-      const float wt = __builtin_exp2f(part_ml[ig * 2] - M);
-      num += wt * part_acc[ig * D + d];
-      den += wt * part_ml[ig * 2 + 1];
+    for (int c0 = 0; c0 < nch; c0 += 8) {
+      float a[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int c = c0 + j < nch ? c0 + j : nch - 1;
+        a[j] = ld_dev(&p.part_acc[(((size_t)base + (size_t)c * p.Hkv + it.kv_head) * G + g) * D + d]);
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        if (c0 + j < nch) {
+          const float wt = __builtin_exp2f(cm[(c0 + j) * G + g] - M);
+          num += wt * a[j];
+          den += wt * cl[(c0 + j) * G + g];
+        }
+      }
     }
-    out[((size_t)s * Hkv * G + (size_t)h * G + g) * D + d] = num / den;
+    orow[e] = num / den;
   }
+  if (threadIdx.x == 0) __hip_atomic_store(done, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next layer
 }
 
 // ---- host ---------------------------------------------------------------------------
@@ -295,7 +355,7 @@ static int check_bound(vkv_pool* p, const void* workspace, const char* who) {
 }
 
 static int launch_slice(vkv_pool* p, int32_t layer, int32_t slice, const void* q, const int32_t* table,
-                        int32_t max_blk, void* workspace, float scale, hipStream_t st) {
+                        int32_t max_blk, void* workspace, void* out, float scale, hipStream_t st) {
   const int32_t first = p->slice_start[slice], count = p->slice_start[slice + 1] - first;
   const int D = p->cfg.head_dim;
   char* ws = (char*)workspace;
@@ -307,12 +367,16 @@ static int launch_slice(vkv_pool* p, int32_t layer, int32_t slice, const void* q
   a.table = table;
   a.part_acc = (float*)(ws + p->ws.part_acc);
   a.part_ml = (float*)(ws + p->ws.part_ml);
+  a.seq_base = (const int32_t*)(ws + p->ws.seq_base);
+  a.done = (int32_t*)(ws + p->ws.done);
+  a.out = (float*)out;
   a.err = (uint32_t*)(ws + p->ws.header);
   a.block_elems = p->block_elems;
   a.v_off = (uint32_t)(p->cfg.num_kv_heads * 16 * D);
   a.item_first = first;
   a.max_blk = max_blk;
   a.Hq = p->cfg.num_q_heads;
+  a.Hkv = p->cfg.num_kv_heads;
   a.G = p->G;
   a.NB = p->cfg.num_blocks;
   a.scale_log2 = (scale != 0.f ? scale : 1.0f / std::sqrt((float)D)) * 1.4426950408889634f;
@@ -326,26 +390,19 @@ static int launch_slice(vkv_pool* p, int32_t layer, int32_t slice, const void* q
 }
 
 static int check_slice_args(vkv_pool* p, int32_t layer, const void* q, const int32_t* table, int32_t max_blk,
-                            void* workspace, const char* who) {
+                            void* workspace, void* out, const char* who) {
   int st = check_bound(p, workspace, who);
   if (st != VKV_OK) return st;
   if (!p->cfg.base) { set_error("%s: pool has no device memory", who); return VKV_E_INVAL; }
   if (layer < 0 || layer >= p->cfg.num_layers) { set_error("%s: layer %d out of range", who, layer); return VKV_E_INVAL; }
-  if (!q || !table || (uintptr_t)q % 16) { set_error("%s: q (16-byte aligned) and block_table must be given", who); return VKV_E_INVAL; }
+  if (!q || !table || !out || (uintptr_t)q % 16) {
+    set_error("%s: q (16-byte aligned), block_table and out must be given", who);
+    return VKV_E_INVAL;
+  }
   if (max_blk < p->max_ctx_blocks) {
     set_error("%s: block table has %d columns, the plan needs %d", who, max_blk, p->max_ctx_blocks);
     return VKV_E_INVAL;
   }
-  return VKV_OK;
-}
-
-static int launch_finalize(vkv_pool* p, void* workspace, void* out, hipStream_t st) {
-  char* ws = (char*)workspace;
-  ProfScope prof(p, VKV_PROF_COMBINE, 0, st);
-  hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)(p->num_seqs * p->cfg.num_kv_heads)), dim3(256), 0, st,
-                     (const float*)(ws + p->ws.part_acc), (const float*)(ws + p->ws.part_ml),
-                     (const int32_t*)(ws + p->ws.seq_base), (float*)out, p->cfg.num_kv_heads, p->G, p->cfg.head_dim);
-  VKV_HIP(hipGetLastError());
   return VKV_OK;
 }
 
@@ -358,8 +415,9 @@ extern "C" {
 int kv_attn_plan(vkv_pool* p, const int32_t* ctx, int32_t S, uint64_t slice_bytes, int32_t chunk_tokens,
                  vkv_attn_plan_info* info) {
   if (!p || !ctx || S < 1) { set_error("kv_attn_plan: bad argument"); return VKV_E_INVAL; }
-  if (chunk_tokens < kGroupTokens || chunk_tokens % kGroupTokens) {
-    set_error("kv_attn_plan: chunk_tokens must be a positive multiple of %d", kGroupTokens);
+  if (chunk_tokens < kGroupTokens || chunk_tokens % kGroupTokens || chunk_tokens > kMaxChunkTokens) {
+    set_error("kv_attn_plan: chunk_tokens must be a multiple of %d in [%d, %d]", kGroupTokens, kGroupTokens,
+              kMaxChunkTokens);
     return VKV_E_INVAL;
   }
   const int Hkv = p->cfg.num_kv_heads, D = p->cfg.head_dim, B = p->cfg.block_tokens;
@@ -371,6 +429,15 @@ int kv_attn_plan(vkv_pool* p, const int32_t* ctx, int32_t S, uint64_t slice_byte
     max_blocks = std::max(max_blocks, (ctx[s] + B - 1) / B);
   }
   if (n_items > 0x7FFFFFF0ll) { set_error("kv_attn_plan: too many work items"); return VKV_E_INVAL; }
+  {
+    // the merge stages (max, sum) of all chunks of one sequence in LDS
+    const int64_t max_chunks = ((int64_t)max_blocks * B + chunk_tokens - 1) / chunk_tokens;
+    if (max_chunks * p->G * 8 > kMergeLdsBytes) {
+      set_error("kv_attn_plan: %lld chunks per sequence is too many for group size %d; raise chunk_tokens",
+                (long long)max_chunks, p->G);
+      return VKV_E_INVAL;
+    }
+  }
   std::vector<WorkItem> work;
   std::vector<int32_t> seq_base((size_t)S + 1);
   work.reserve((size_t)n_items);
@@ -404,7 +471,7 @@ int kv_attn_plan(vkv_pool* p, const int32_t* ctx, int32_t S, uint64_t slice_byte
   p->num_seqs = S;
   p->chunk_tokens = chunk_tokens;
   p->max_ctx_blocks = max_blocks;
-  p->ws = workspace_layout((int64_t)p->work.size(), S, p->G, D);
+  p->ws = workspace_layout((int64_t)p->work.size(), S, Hkv, p->G, D);
   p->has_plan = true;
   ++p->plan_gen;
   if (info) {
@@ -437,7 +504,7 @@ int kv_attn_bind(vkv_pool* p, void* workspace, uint64_t workspace_bytes, void* s
   int st = ensure_stage(p, p->ws.upload_bytes);
   if (st != VKV_OK) return st;
   char* h = (char*)p->stage;
-  std::memset(h, 0, 256);
+  std::memset(h, 0, p->ws.upload_bytes);   // flag word and per-(sequence, kv head) counters start at zero
   std::memcpy(h + p->ws.work, p->work.data(), p->work.size() * sizeof(WorkItem));
   std::memcpy(h + p->ws.seq_base, p->seq_base.data(), p->seq_base.size() * 4);
   VKV_HIP(hipMemcpyAsync(workspace, h, p->ws.upload_bytes, hipMemcpyHostToDevice, (hipStream_t)stream));
@@ -449,21 +516,14 @@ int kv_attn_bind(vkv_pool* p, void* workspace, uint64_t workspace_bytes, void* s
 }
 
 int paged_decode_attn_slice(vkv_pool* p, int32_t layer, int32_t slice, const void* q, const int32_t* table,
-                            int32_t max_blk, void* workspace, float scale, void* stream) {
-  int st = check_slice_args(p, layer, q, table, max_blk, workspace, "paged_decode_attn_slice");
+                            int32_t max_blk, void* workspace, void* out, float scale, void* stream) {
+  int st = check_slice_args(p, layer, q, table, max_blk, workspace, out, "paged_decode_attn_slice");
   if (st != VKV_OK) return st;
   if (slice < 0 || slice >= (int32_t)p->slice_start.size() - 1) {
     set_error("paged_decode_attn_slice: slice %d out of range [0,%d)", slice, (int)p->slice_start.size() - 1);
     return VKV_E_INVAL;
   }
-  return launch_slice(p, layer, slice, q, table, max_blk, workspace, scale, (hipStream_t)stream);
-}
-
-int kv_attn_finalize(vkv_pool* p, void* workspace, void* out, void* stream) {
-  int st = check_bound(p, workspace, "kv_attn_finalize");
-  if (st != VKV_OK) return st;
-  if (!out) { set_error("kv_attn_finalize: null output"); return VKV_E_INVAL; }
-  return launch_finalize(p, workspace, out, (hipStream_t)stream);
+  return launch_slice(p, layer, slice, q, table, max_blk, workspace, out, scale, (hipStream_t)stream);
 }
 
 int kv_attn_check(vkv_pool* p, void* workspace, void* stream) {
@@ -479,11 +539,11 @@ int kv_attn_check(vkv_pool* p, void* workspace, void* stream) {
 int kv_attn_run_layer(vkv_pool* p, int32_t layer, int32_t* cursor, const void* q, const int32_t* table,
                       int32_t max_blk, void* workspace, void* out, float scale, int32_t max_inflight,
                       void* stream) {
-  int st = check_slice_args(p, layer, q, table, max_blk, workspace, "kv_attn_run_layer");
+  int st = check_slice_args(p, layer, q, table, max_blk, workspace, out, "kv_attn_run_layer");
   if (st != VKV_OK) return st;
   const int32_t n_slices = (int32_t)p->slice_start.size() - 1;
-  if (!cursor || !out || *cursor < 0 || *cursor > n_slices || max_inflight < 1 || max_inflight > kMaxInflight) {
-    set_error("kv_attn_run_layer: bad cursor, output or max_inflight");
+  if (!cursor || *cursor < 0 || *cursor > n_slices || max_inflight < 1 || max_inflight > kMaxInflight) {
+    set_error("kv_attn_run_layer: bad cursor or max_inflight");
     return VKV_E_INVAL;
   }
   hipStream_t hs = (hipStream_t)stream;
@@ -522,12 +582,9 @@ int kv_attn_run_layer(vkv_pool* p, int32_t layer, int32_t* cursor, const void* q
       return VKV_YIELDED;
     }
     if ((st = admit()) != VKV_OK) return st;
-    if ((st = launch_slice(p, layer, s, q, table, max_blk, workspace, scale, hs)) != VKV_OK) return st;
+    if ((st = launch_slice(p, layer, s, q, table, max_blk, workspace, out, scale, hs)) != VKV_OK) return st;
     if ((st = track()) != VKV_OK) return st;
   }
-  if ((st = admit()) != VKV_OK) return st;
-  if ((st = launch_finalize(p, workspace, out, hs)) != VKV_OK) return st;
-  if ((st = track()) != VKV_OK) return st;
   *cursor = n_slices;
   return VKV_OK;
 }

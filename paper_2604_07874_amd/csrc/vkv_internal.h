@@ -26,6 +26,8 @@ int  hip_fail(hipError_t e, const char* what);
 
 constexpr int kMaxInflight = 8;
 constexpr int kGroupTokens = 32;   // tokens one wave handles per loop iteration (two blocks)
+constexpr int kMergeLdsBytes = 16 * 1024;   // LDS the last chunk may use for per-chunk (max, sum)
+constexpr int kMaxChunkTokens = 2048;   // an item's block ids fit two registers per lane
 
 struct WorkItem {   // matches int4 on the device
   int32_t seq, kv_head, first_block, n_tokens;
@@ -36,20 +38,22 @@ struct WorkspaceLayout {
   uint64_t header = 0;       // 256 bytes; word 0 = bad-table-entry flag
   uint64_t work = 0;         // WorkItem[n_items]
   uint64_t seq_base = 0;     // int32[num_seqs + 1]: first item of each sequence
+  uint64_t done = 0;         // int32[num_seqs][kv_heads]: chunks finished in the current layer
   uint64_t part_ml = 0;      // float[n_items][G][2]: running max (log2 units), sum of exponentials
   uint64_t part_acc = 0;     // float[n_items][G][D]: exp-weighted sum of V rows
   uint64_t total = 0;
-  uint64_t upload_bytes = 0; // header + work + seq_base are written by kv_attn_bind
+  uint64_t upload_bytes = 0; // header + work + seq_base + done are written by kv_attn_bind
 };
 
 inline uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 
-inline WorkspaceLayout workspace_layout(int64_t n_items, int64_t num_seqs, int G, int D) {
+inline WorkspaceLayout workspace_layout(int64_t n_items, int64_t num_seqs, int Hkv, int G, int D) {
   WorkspaceLayout w;
   w.header = 0;
   w.work = 256;
   w.seq_base = w.work + (uint64_t)n_items * sizeof(WorkItem);
-  w.upload_bytes = w.seq_base + (uint64_t)(num_seqs + 1) * 4;
+  w.done = w.seq_base + (uint64_t)(num_seqs + 1) * 4;
+  w.upload_bytes = w.done + (uint64_t)num_seqs * Hkv * 4;
   w.part_ml = align_up(w.upload_bytes, 256);
   w.part_acc = align_up(w.part_ml + (uint64_t)n_items * G * 2 * 4, 256);
   w.total = align_up(w.part_acc + (uint64_t)n_items * G * D * 4, 256);

@@ -169,12 +169,9 @@ def test_yield_resume_is_bit_identical_at_every_slice():
         # a yield request pending before slice k: stop there, resume, same bits
         for k in range(info.n_slices):
             out.fill_(float("nan"))
-            st, cur = vkv.kv_attn_run_layer(c.pool, 0, 0, q_t, c.tables_t, c.ws, out) if k == 0 else (None, 0)
-            out.fill_(float("nan"))
-            cur = 0
             # run slices [0,k) one by one, then request the yield
             for s in range(k):
-                vkv.paged_decode_attn_slice(c.pool, 0, s, q_t, c.tables_t, c.ws)
+                vkv.paged_decode_attn_slice(c.pool, 0, s, q_t, c.tables_t, c.ws, out)
             vkv.kv_yield_request(c.pool)
             st, cur = vkv.kv_attn_run_layer(c.pool, 0, k, q_t, c.tables_t, c.ws, out)
             assert (st, cur) == (vkv.VKV_YIELDED, k) and vkv.kv_yield_pending(c.pool)
@@ -198,7 +195,7 @@ def test_reclaim_between_slices_keeps_attention_bitwise():
         out = torch.empty((c.wl.num_seqs, g.num_q_heads, g.head_dim), dtype=torch.float32, device="cuda:0")
         k = info.n_slices // 2
         for s in range(k):
-            vkv.paged_decode_attn_slice(c.pool, 1, s, q_t, c.tables_t, c.ws)
+            vkv.paged_decode_attn_slice(c.pool, 1, s, q_t, c.tables_t, c.ws, out)
         copy_stream = torch.cuda.Stream()
         stats = vkv.kv_reclaim_range(c.pool, lo, hi, c.tables_t, c.remap_t, chunk_bytes=c.wl.chunk_bytes,
                                      copy_stream=copy_stream, decode_stream=torch.cuda.current_stream())

@@ -367,7 +367,10 @@ def unused_slot_spans(st: PoolState):
 
 
 def poison_unused_slots(st: PoolState, pool_flat) -> None:
-    """Write bf16 NaN into slots past each sequence's length (numpy uint16 or torch int16 view)."""
-    nan = BF16_NAN_BITS
-    for o, n in unused_slot_spans(st):
-        pool_flat[o:o + n] = nan
+    """Write bf16 NaN into slots past each sequence's length (numpy uint16 or torch int16, flat)."""
+    g = st.geom
+    shape = (g.num_blocks, g.num_layers, 2, g.num_kv_heads, g.block_tokens, g.head_dim)
+    n = g.pool_elems
+    view = pool_flat[:n].reshape(shape) if isinstance(pool_flat, np.ndarray) else pool_flat[:n].view(shape)
+    for blk, used in st.poisoned:
+        view[blk, :, :, :, used:, :] = BF16_NAN_BITS

@@ -30,6 +30,20 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published
 
 
+def measured_traffic_ratio(workload: str):
+    """HBM bytes / algorithmic bytes of the attention kernel from the committed counter run,
+    or None when there is none for this workload or the kernel source has changed since."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    src = os.path.join(ROOT, "paper_2604_07874_amd", "csrc", "attn.hip")
+    if not (os.path.exists(path) and os.path.exists(src)):
+        return None
+    kv = dict(l.split(":", 1) for l in open(path) if l.startswith("attn_"))
+    if kv.get("attn_source_sha256", "").strip() != hashlib.sha256(open(src, "rb").read()).hexdigest():
+        return None
+    return float(kv["attn_traffic_ratio"])
+
+
 def percentile(a, q):
     return float(np.percentile(np.asarray(a, dtype=np.float64), q)) if len(a) else None
 
@@ -152,18 +166,21 @@ def main():
         slice_ms_avg = float(sl["ms"].mean())
         bytes_per_launch = decode_bytes_layer / info.n_slices
         ach = bytes_per_launch / (slice_ms_avg * 1e-3) / 1e9
+        ratio = measured_traffic_ratio(wl.name)
         roofline = {"kernel": "paged_decode_attn_slice_kernel", "bound": "hbm", "achieved": round(ach, 1),
                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4),
-                    "traffic": None, "avg_launch_us": round(slice_ms_avg * 1e3, 2),
+                    "traffic": None if ratio is None else int(ratio * bytes_per_launch), "avg_launch_us": round(slice_ms_avg * 1e3, 2),
                     "bytes_per_launch": int(bytes_per_launch), "launches": int(n_slice_launches)}
-        if len(rl):
-            rl_ms = float(rl["ms"].sum()) / args.steps
-            rach = reclaim_traffic / (rl_ms * 1e-3) / 1e9
+        if len(rl) and int(rl["index"].sum()) > 0:
+            n_launches = int(rl["index"].sum())
+            rl_ms = float(rl["ms"].sum())                    # all copy launches, gaps between them included
+            per_launch_ms = rl_ms / n_launches
+            per_launch_bytes = reclaim_traffic * len(rl) / n_launches
+            rach = per_launch_bytes / (per_launch_ms * 1e-3) / 1e9
             roofline_reclaim = {"kernel": "kv_block_relocate_kernel", "bound": "hbm", "achieved": round(rach, 1),
                                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(rach / HBM_PEAK_GBPS, 4),
-                                "traffic": None, "avg_launch_us": round(float(rl["ms"].mean()) * 1e3, 2),
-                                "bytes_per_launch": int(reclaim_traffic / (len(rl) / args.steps)),
-                                "launches": int(len(rl))}
+                                "traffic": None, "avg_launch_us": round(per_launch_ms * 1e3, 2),
+                                "bytes_per_launch": int(per_launch_bytes), "launches": n_launches}
         extra.update({
             "slice_us_p50": round(percentile(sl["ms"], 50) * 1e3, 1),
             "slice_us_p99": round(percentile(sl["ms"], 99) * 1e3, 1),

@@ -247,7 +247,8 @@ int block_table_rewrite(int32_t* tables_dev, int64_t n_entries, const int32_t* r
 /* ---- per-launch timing ---------------------------------------------------- */
 
 #define VKV_PROF_SLICE    0   /* paged_decode_attn_slice kernel; index = slice */
-#define VKV_PROF_RELOCATE 1   /* block copy launch; index = chunk number */
+#define VKV_PROF_RELOCATE 1   /* all block copy launches of one kv_reclaim_range call;
+                                 index = number of launches */
 #define VKV_PROF_REWRITE  2   /* table rewrite kernel */
 
 typedef struct vkv_profile_record {

@@ -11,6 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvalvekv.so")
 SOURCES = ["pool.hip", "attn.hip", "reclaim.hip"]
+DRIVER = os.path.join(HERE, "vkv_pmc_driver")
 
 
 def hipcc_path() -> str:
@@ -40,7 +41,24 @@ def build(verbose: bool = True) -> str:
     if verbose and err.strip():
         print(err, file=sys.stderr)
     os.replace(tmp, LIB)
+    build_driver(verbose)
     return LIB
+
+
+def build_driver(verbose: bool = True) -> str:
+    """The native counter-run driver / call-sequence example, linked against the library."""
+    cmd = [hipcc_path(), "--offload-arch=gfx950", "-O2", "-std=c++17", "-Wno-unused-command-line-argument",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-I", os.path.join(ROOT, "include"), os.path.join(CSRC, "pmc_driver.hip"),
+           "-L", HERE, "-lvalvekv", "-Wl,-rpath,$ORIGIN", "-o", DRIVER + ".tmp"]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        noise = "is not a recognized feature for this target"
+        raise RuntimeError("hipcc failed (driver):\n" + "\n".join(l for l in res.stderr.splitlines() if noise not in l))
+    os.replace(DRIVER + ".tmp", DRIVER)
+    return DRIVER
 
 
 if __name__ == "__main__":

@@ -1,0 +1,139 @@
+// Native driver for hardware-counter runs: the Llama-3-8B-shaped decode + reclamation step
+// through the C ABI, with no Python in the process (rocprofv3 --pmc -- ./vkv_pmc_driver).
+// It is also the smallest complete example of the call sequence a framework would use.
+//
+//   vkv_pmc_driver [layers=32] [steps=2] [pool_GiB=40]
+//
+// Inputs are synthetic: contexts ~ lognormal(median 2048, sigma 0.7) clipped to [16, 8192],
+// 64 sequences, 32 query / 8 KV heads of 128, 70 % of the pool's 2 MiB blocks live at random
+// positions, the top 10 % of the pool reclaimed.  Values are a cheap integer hash turned into
+// small bf16 numbers; counters do not depend on them.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+#include <numeric>
+#include <random>
+#include <vector>
+
+#include "valvekv.h"
+
+#define CK(x)                                                                        \
+  do {                                                                               \
+    hipError_t e_ = (x);                                                             \
+    if (e_ != hipSuccess) {                                                          \
+      std::fprintf(stderr, "%s failed: %s\n", #x, hipGetErrorString(e_));            \
+      std::exit(1);                                                                  \
+    }                                                                                \
+  } while (0)
+#define VK(x)                                                                        \
+  do {                                                                               \
+    int s_ = (x);                                                                    \
+    if (s_ < 0) {                                                                    \
+      std::fprintf(stderr, "%s failed (%d): %s\n", #x, s_, vkv_last_error());        \
+      std::exit(1);                                                                  \
+    }                                                                                \
+  } while (0)
+
+// bf16 values in (-2, 2) from a hash of the element index
+__global__ void fill_bf16(uint16_t* p, size_t n, uint32_t seed) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) {
+    uint32_t h = (uint32_t)i * 2654435761u ^ (uint32_t)(i >> 32) ^ seed;
+    h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+    p[i] = (uint16_t)(((h & 0x8000u)) | 0x3F00u | (h & 0xFFu));   // sign, exponent of 0.5..2, 8 mantissa bits (7 used)
+  }
+}
+
+int main(int argc, char** argv) {
+  const int L = argc > 1 ? std::atoi(argv[1]) : 32;
+  const int steps = argc > 2 ? std::atoi(argv[2]) : 2;
+  const int pool_gib = argc > 3 ? std::atoi(argv[3]) : 40;
+  const int S = 64, Hq = 32, Hkv = 8, D = 128, B = 16;
+  const size_t block_elems = (size_t)L * 2 * Hkv * B * D;
+  const size_t block_bytes = block_elems * 2;
+  const int bph = 32;
+  const int NB = (int)(((size_t)pool_gib << 30) / block_bytes / bph * bph);
+  const int max_blk = 8192 / B;
+
+  std::mt19937_64 rng(0);
+  std::lognormal_distribution<double> ln(std::log(2048.0), 0.7);
+  std::vector<int32_t> ctx(S);
+  for (auto& c : ctx) c = (int32_t)std::min(8192.0, std::max(16.0, std::nearbyint(ln(rng))));
+  std::vector<int32_t> ids(NB);
+  std::iota(ids.begin(), ids.end(), 0);
+  std::shuffle(ids.begin(), ids.end(), rng);
+  const int n_live = (int)(0.7 * NB);
+  std::vector<int32_t> tables((size_t)S * max_blk, -1);
+  size_t cur = 0;
+  for (int s = 0; s < S; ++s)
+    for (int j = 0; j < (ctx[s] + B - 1) / B; ++j) tables[(size_t)s * max_blk + j] = ids[cur++];
+  if ((int)cur > n_live) { std::fprintf(stderr, "batch does not fit\n"); return 1; }
+  // background blocks get table rows of their own
+  const size_t bg = n_live - cur, bg_rows = (bg + max_blk - 1) / max_blk;
+  tables.resize((size_t)(S + bg_rows) * max_blk, -1);
+  for (size_t i = 0; i < bg; ++i) tables[(size_t)S * max_blk + i] = ids[cur + i];
+
+  uint16_t *pool_d, *q_d;
+  int32_t *tables_d, *tables0_d, *remap_d;
+  float* out_d;
+  CK(hipMalloc(&pool_d, (size_t)NB * block_bytes));
+  CK(hipMalloc(&q_d, (size_t)L * S * Hq * D * 2));
+  CK(hipMalloc(&tables_d, tables.size() * 4));
+  CK(hipMalloc(&tables0_d, tables.size() * 4));
+  CK(hipMalloc(&remap_d, (size_t)NB * 4));
+  CK(hipMalloc(&out_d, (size_t)S * Hq * D * 4));
+  hipLaunchKernelGGL(fill_bf16, dim3(8192), dim3(256), 0, 0, pool_d, (size_t)NB * block_elems, 1u);
+  hipLaunchKernelGGL(fill_bf16, dim3(256), dim3(256), 0, 0, q_d, (size_t)L * S * Hq * D, 2u);
+  CK(hipMemcpy(tables0_d, tables.data(), tables.size() * 4, hipMemcpyHostToDevice));
+  CK(hipMemcpy(tables_d, tables0_d, tables.size() * 4, hipMemcpyDeviceToDevice));
+  CK(hipDeviceSynchronize());
+
+  vkv_pool_config cfg{};
+  cfg.num_layers = L; cfg.num_q_heads = Hq; cfg.num_kv_heads = Hkv; cfg.head_dim = D; cfg.block_tokens = B;
+  cfg.num_blocks = NB; cfg.blocks_per_handle = bph; cfg.base = pool_d; cfg.bytes = (uint64_t)NB * block_bytes;
+  vkv_pool* pool = nullptr;
+  VK(kv_pool_init(&cfg, &pool));
+  std::vector<int32_t> live_ids(ids.begin(), ids.begin() + n_live);
+  VK(kv_pool_adopt(pool, live_ids.data(), n_live));
+
+  vkv_attn_plan_info info{};
+  VK(kv_attn_plan(pool, ctx.data(), S, 1ull << 30, 1024, &info));
+  void* ws;
+  CK(hipMalloc(&ws, info.workspace_bytes));
+  VK(kv_attn_bind(pool, ws, info.workspace_bytes, nullptr));
+  const int lo = (NB - NB / 10) / bph * bph, hi = NB;
+  vkv_reclaim_stats rs{};
+  std::vector<int32_t> remap_h(NB);
+  VK(kv_reclaim_plan(pool, lo, hi, remap_h.data(), &rs));
+  std::vector<int32_t> src, dst;
+  for (int b = lo; b < hi; ++b)
+    if (remap_h[b] != b) { src.push_back(b); dst.push_back(remap_h[b]); }
+
+  std::printf("L=%d S=%d pool=%d blocks of %zu KiB; items %d slices %d; kv bytes/layer %llu; "
+              "reclaim [%d,%d): %d blocks = %llu bytes moved\n",
+              L, S, NB, block_bytes >> 10, info.n_items, info.n_slices,
+              (unsigned long long)info.kv_bytes_per_layer, lo, hi, rs.blocks_moved, (unsigned long long)rs.bytes_moved);
+  for (int step = 0; step < steps; ++step) {
+    for (int layer = 0; layer < L; ++layer) {
+      int32_t cursor = 0;
+      VK(kv_attn_run_layer(pool, layer, &cursor, q_d + (size_t)layer * S * Hq * D, tables_d, max_blk, ws, out_d, 0.f, 2,
+                           nullptr));
+    }
+    VK(kv_reclaim_range(pool, lo, hi, tables_d, (int64_t)tables.size(), 0, 0, nullptr, nullptr, remap_d, 0, &rs));
+    // the online tenant returns the range; rewind the bookkeeping (the sources were left intact)
+    VK(kv_pool_return_range(pool, lo, hi));
+    VK(kv_pool_free(pool, dst.data(), (int32_t)dst.size()));
+    VK(kv_pool_adopt(pool, src.data(), (int32_t)src.size()));
+    CK(hipMemcpy(tables_d, tables0_d, tables.size() * 4, hipMemcpyDeviceToDevice));
+  }
+  VK(kv_attn_check(pool, ws, nullptr));
+  CK(hipDeviceSynchronize());
+  VK(kv_pool_destroy(pool));
+  std::printf("done\n");
+  return 0;
+}

@@ -14,34 +14,33 @@ namespace vkv {
 // ---- kernels ----------------------------------------------------------------------
 
 constexpr int kCopyThreads = 256;
-constexpr int kCopyUnroll = 4;                                   // 16-byte vectors in flight per thread
-constexpr uint32_t kPieceVecs = kCopyThreads * kCopyUnroll * 2;  // 32 KiB per workgroup
+constexpr int kCopyUnroll = 16;                              // 16-byte vectors in flight per thread
+constexpr uint32_t kPieceVecs = kCopyThreads * kCopyUnroll;  // 64 KiB per workgroup
 
-// One workgroup copies one piece of one live block of [first_src, first_src + gridDim.x)
-// to remap[src].  Blocks with remap[src] == src (free, nothing to move) exit at once.
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
+// One workgroup copies one 64 KiB piece of one live block of [first_src, first_src + gridDim.x)
+// to remap[src]: 16 loads per thread in flight, then 16 stores, all non-temporal (the data
+// is not read again soon).  Blocks with remap[src] == src (free, nothing to move) exit at once.
 __global__ __launch_bounds__(kCopyThreads) void kv_block_relocate_kernel(
     u32x4* __restrict__ pool, const int32_t* __restrict__ remap, int32_t first_src,
-    uint32_t block_vecs /* uint4 per block */) {
+    uint32_t block_vecs /* 16-byte vectors per block */) {
   const int32_t src = first_src + (int32_t)blockIdx.x;
   const int32_t dst = remap[src];
   if (dst == src) return;
-  const uint32_t v0 = blockIdx.y * kPieceVecs;
+  const uint32_t v0 = blockIdx.y * kPieceVecs + threadIdx.x;
   const u32x4* __restrict__ s = pool + (size_t)src * block_vecs;
   u32x4* __restrict__ d = pool + (size_t)dst * block_vecs;
+  u32x4 r[kCopyUnroll];
 #pragma unroll
-  for (uint32_t it = 0; it < 2; ++it) {
-    u32x4 r[kCopyUnroll];
-    uint32_t idx[kCopyUnroll];
+  for (int u = 0; u < kCopyUnroll; ++u) {
+    const uint32_t i = v0 + u * kCopyThreads;
+    if (i < block_vecs) r[u] = __builtin_nontemporal_load(s + i);
+  }
 #pragma unroll
-    for (int u = 0; u < kCopyUnroll; ++u) {
-      idx[u] = v0 + (it * kCopyUnroll + u) * kCopyThreads + threadIdx.x;
-      if (idx[u] < block_vecs) r[u] = __builtin_nontemporal_load(s + idx[u]);
-    }
-#pragma unroll
-    for (int u = 0; u < kCopyUnroll; ++u)
-      if (idx[u] < block_vecs) __builtin_nontemporal_store(r[u], d + idx[u]);
+  for (int u = 0; u < kCopyUnroll; ++u) {
+    const uint32_t i = v0 + u * kCopyThreads;
+    if (i < block_vecs) __builtin_nontemporal_store(r[u], d + i);
   }
 }
 
@@ -174,6 +173,10 @@ int kv_reclaim_range(vkv_pool* p, int32_t lo, int32_t hi, int32_t* tables, int64
   const size_t per_chunk = chunk_bytes ? std::max<uint64_t>(1, chunk_bytes / p->block_bytes) : src.size();
   int32_t n_chunks = 0;
   uint64_t sent = 0;
+  const int32_t planned_chunks = per_chunk ? (int32_t)((src.size() + per_chunk - 1) / per_chunk) : 0;
+  {
+  // one timing record brackets all copy launches of this call (index = number of launches)
+  ProfScope prof(p, VKV_PROF_RELOCATE, planned_chunks, cs);
   for (size_t i = 0; i < src.size(); i += per_chunk) {
     const size_t j = std::min(src.size(), i + per_chunk);
     if (rate_cap) {
@@ -182,13 +185,13 @@ int kv_reclaim_range(vkv_pool* p, int32_t lo, int32_t hi, int32_t* tables, int64
       std::this_thread::sleep_until(due);
     }
     const int32_t first = src[i], last = src[j - 1];
-    ProfScope prof(p, VKV_PROF_RELOCATE, n_chunks, cs);
     hipLaunchKernelGGL(kv_block_relocate_kernel, dim3((unsigned)(last - first + 1), pieces), dim3(kCopyThreads), 0,
                        cs, (u32x4*)p->cfg.base, (const int32_t*)remap_dev, first, block_vecs);
     he = hipGetLastError();
     if (he != hipSuccess) return fail(hip_fail(he, "kv_block_relocate launch"));
     sent += (uint64_t)(j - i) * p->block_bytes;
     ++n_chunks;
+  }
   }
   if (launch_rewrite(p, tables, n_entries, remap_dev, nb, cs) != VKV_OK) return fail(VKV_E_HIP);
 

@@ -99,10 +99,10 @@ class Workload:
     ctx_dist: Tuple  # ("uniform", lo, hi) | ("lognormal", median, sigma, lo, cap)
     occupancy: Optional[float]  # fraction of pool blocks live; None = decode batch only
     reclaim_blocks: int  # size of the highest-address range handed to the online tenant
-    chunk_bytes: int = 64 << 20
+    chunk_bytes: int = 0  # live bytes per copy launch; 0 = one launch
     rate_cap: float = 0.0  # bytes/s of live data copied; 0 = uncapped
     slice_bytes: int = 1 << 30
-    chunk_tokens: int = 512
+    chunk_tokens: int = 1024  # tokens of one kv head handled by one workgroup
     shared_prefix_blocks: int = 0  # sequence 1 shares this many leading blocks with sequence 0
 
     @property
@@ -131,7 +131,7 @@ WORKLOADS: Dict[str, Workload] = {
     "llama8b": Workload("llama8b", _g(32, 32, 8, 128, 20480, 32), 64,
                         ("lognormal", 2048, 0.7, 16, 8192), 0.70, 2048),
     "offline_batch": Workload("offline_batch", _g(8, 32, 8, 128, 327680, 128), 256,
-                              ("uniform", 512, 32768), None, 16384, rate_cap=20e9),
+                              ("uniform", 512, 32768), None, 16384, chunk_bytes=64 << 20, rate_cap=20e9),
     "llama70b_tp8": Workload("llama70b_tp8", _g(80, 8, 1, 128, 104832, 64), 128,
                              ("lognormal", 4096, 0.7, 16, 16384), 0.85, 13120),
     "stress": Workload("stress", _g(10, 32, 8, 128, 327680, 64), 512,

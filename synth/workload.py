@@ -101,7 +101,7 @@ class Workload:
     reclaim_blocks: int  # size of the highest-address range handed to the online tenant
     chunk_bytes: int = 0  # live bytes per copy launch; 0 = one launch
     rate_cap: float = 0.0  # bytes/s of live data copied; 0 = uncapped
-    slice_bytes: int = 1 << 30
+    slice_bytes: int = 512 << 20  # K+V bytes per attention launch; bounds the yield latency
     chunk_tokens: int = 1024  # tokens of one kv head handled by one workgroup
     shared_prefix_blocks: int = 0  # sequence 1 shares this many leading blocks with sequence 0
 

@@ -60,6 +60,9 @@ def main():
     ap.add_argument("--reclaim-chunk-bytes", type=int, default=None)
     ap.add_argument("--max-inflight", type=int, default=2)
     ap.add_argument("--yield-injections", type=int, default=1000)
+    ap.add_argument("--concurrent-reclaim", action="store_true",
+                    help="extra leg: rate-capped, chunked reclamation on a second stream while decode runs")
+    ap.add_argument("--rate-cap", type=float, default=None, help="bytes/s for the concurrent leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-launch-events", action="store_true",
                     help="do not bracket launches with timing events (roofline fields become null)")
@@ -259,6 +262,50 @@ def main():
         extra.update({"yield_latency_us_p50": round(percentile(lat, 50), 1),
                       "yield_latency_us_p99": round(percentile(lat, 99), 1),
                       "yield_latency_us_max": round(max(lat), 1), "yield_injections": len(lat)})
+
+    # ---- optional: reclamation under a rate cap on a second stream while decode keeps running
+    if args.concurrent_reclaim:
+        cap = args.rate_cap or wl.rate_cap or 20e9
+        cchunk = rc_chunk or (64 << 20)
+        decode_stream, copy_stream = torch.cuda.Stream(), torch.cuda.Stream()
+        torch.cuda.synchronize()
+        stop = threading.Event()
+        marks = []          # (time, layers finished) samples from the decode thread
+
+        def decode_forever():
+            n = 0
+            while not stop.is_set():
+                for layer in range(L):
+                    vkv.kv_attn_run_layer(pool, layer, 0, q_all[layer], tables, ws, out[layer],
+                                          max_inflight=args.max_inflight, stream=decode_stream)
+                    n += 1
+                decode_stream.synchronize()
+                marks.append((time.perf_counter(), n))
+
+        th = threading.Thread(target=decode_forever)
+        th.start()
+        while len(marks) < 2:
+            time.sleep(0.001)
+        t_a, n_a = marks[-1]
+        crs = vkv.kv_reclaim_range(pool, lo, hi, tables, remap, chunk_bytes=cchunk, rate_cap_bytes_per_s=int(cap),
+                                   copy_stream=copy_stream, decode_stream=decode_stream)
+        while marks[-1][0] < t_a + crs.host_seconds:
+            time.sleep(0.001)
+        t_b, n_b = marks[-1]
+        stop.set()
+        th.join()
+        torch.cuda.synchronize()
+        vkv.kv_pool_return_range(pool, lo, hi)
+        vkv.kv_pool_free(pool, dst_ids)
+        vkv.kv_pool_adopt(pool, src_ids)
+        tables.copy_(tables0)
+        extra.update({
+            "concurrent_rate_cap_GBps": cap / 1e9,
+            "concurrent_reclaim_achieved_GBps": round(crs.bytes_moved / crs.host_seconds / 1e9, 2),
+            "concurrent_reclaim_ms": round(crs.host_seconds * 1e3, 2),
+            "concurrent_reclaim_launches": int(crs.n_chunks),
+            "concurrent_decode_GBps": round((n_b - n_a) * decode_bytes_layer / (t_b - t_a) / 1e9, 1),
+        })
 
     # ---- the CPU oracle on a bounded sample of the same workload --------------------
     cpu_baseline = None

@@ -29,9 +29,12 @@
  *   - Streams are hipStream_t passed as void* (NULL = the default stream).
  *     Device work is enqueued on the given stream; unless stated otherwise a
  *     call returns without waiting for it.
- *   - One host thread at a time may call into a given pool, except
- *     kv_yield_request / kv_yield_clear / kv_yield_pending, which are safe from
- *     any thread at any time.
+ *   - A pool may be driven by two host threads at once: one "decode" thread
+ *     (kv_attn_plan / bind / check, paged_decode_attn_slice, kv_attn_run_layer)
+ *     and one "memory" thread (kv_pool_*, kv_reclaim_*); the two groups touch
+ *     disjoint state.  Within a group, one thread at a time.
+ *     kv_yield_request / kv_yield_clear / kv_yield_pending are safe from any
+ *     thread at any time.
  *
  * Pool layout (bf16 elements, block-major so that a block-id range is an
  * address range):   pool[block][layer][K=0|V=1][kv_head][slot][d]

@@ -229,6 +229,7 @@ int kv_profile_enable(vkv_pool* p, int32_t max_records) {
   p->prof_tag.clear();
   p->prof_cap = 0;
   p->prof_ev.reserve((size_t)max_records * 2);
+  p->prof_tag.reserve((size_t)max_records);
   for (int32_t i = 0; i < 2 * max_records; ++i) {
     hipEvent_t e = nullptr;
     VKV_HIP(hipEventCreate(&e));

@@ -7,6 +7,7 @@
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
+#include <mutex>
 #include <string>
 #include <utility>
 #include <vector>
@@ -110,6 +111,7 @@ struct vkv_pool {
   std::vector<hipEvent_t> prof_ev;      // 2 per record: start, end
   std::vector<std::pair<int32_t, int32_t>> prof_tag;   // (kind, index)
   int32_t prof_cap = 0;
+  std::mutex prof_mu;                  // the decode thread and the reclaim thread may both record
 
   bool broken = false;   // a HIP call failed mid-operation
 };
@@ -126,11 +128,14 @@ struct ProfScope {
   hipStream_t st;
   int slot = -1;
   ProfScope(vkv_pool* pool, int32_t kind, int32_t index, hipStream_t stream) : p(pool), st(stream) {
-    if (p->prof_cap > 0 && (int32_t)p->prof_tag.size() < p->prof_cap) {
-      slot = (int)p->prof_tag.size();
-      p->prof_tag.emplace_back(kind, index);
-      (void)hipEventRecord(p->prof_ev[2 * slot], st);
+    if (p->prof_cap > 0) {
+      std::lock_guard<std::mutex> g(p->prof_mu);
+      if ((int32_t)p->prof_tag.size() < p->prof_cap) {
+        slot = (int)p->prof_tag.size();
+        p->prof_tag.emplace_back(kind, index);
+      }
     }
+    if (slot >= 0) (void)hipEventRecord(p->prof_ev[2 * slot], st);
   }
   ~ProfScope() {
     if (slot >= 0) (void)hipEventRecord(p->prof_ev[2 * slot + 1], st);

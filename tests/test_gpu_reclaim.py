@@ -259,3 +259,64 @@ def test_rate_cap_is_respected():
               f"({stats.bytes_moved / stats.host_seconds / 1e9:.2f} GB/s, cap {cap / 1e9} GB/s)", flush=True)
     finally:
         c.close()
+
+
+def test_rate_capped_reclaim_while_decode_runs_on_another_stream():
+    """The offline-batch shape's scenario: decode keeps running on its stream (its own host thread)
+    while the range is emptied in small launches under a rate cap on a second stream."""
+    c = make_case("offline_batch_small", 12, occupancy=0.8)
+    try:
+        g, vkv = c.wl.geom, c.vkv
+        orc = oracle_for(c)
+        info = c.plan(slice_bytes=1 << 20)
+        L = g.num_layers
+        qs = [c.q_dev(l)[1] for l in range(L)]
+        base = [torch.from_numpy(c.attention(l, qs[l])).cuda() for l in range(L)]
+        decode_stream, copy_stream = torch.cuda.Stream(), torch.cuda.Stream()
+        torch.cuda.synchronize()
+        stop = threading.Event()
+        result = {"passes": 0, "bad": 0, "error": None}
+
+        def decode_loop():
+            try:
+                out = torch.empty_like(base[0])
+                with torch.cuda.stream(decode_stream):
+                    while not stop.is_set() or result["passes"] < 3:
+                        for l in range(L):
+                            out.fill_(float("nan"))
+                            st_, cur = vkv.kv_attn_run_layer(c.pool, l, 0, qs[l], c.tables_t, c.ws, out,
+                                                             stream=decode_stream)
+                            assert st_ == vkv.VKV_OK
+                            decode_stream.synchronize()
+                            if not torch.equal(out, base[l]):
+                                result["bad"] += 1
+                        result["passes"] += 1
+            except Exception as e:          # surfaced by the main thread
+                result["error"] = e
+
+        th = threading.Thread(target=decode_loop)
+        th.start()
+        time.sleep(0.01)
+        lo, hi = c.wl.reclaim_range
+        cap = 1e9
+        stats = vkv.kv_reclaim_range(c.pool, lo, hi, c.tables_t, c.remap_t, chunk_bytes=1 << 20,
+                                     rate_cap_bytes_per_s=int(cap), copy_stream=copy_stream,
+                                     decode_stream=decode_stream)
+        passes_during = result["passes"]
+        # the online tenant overwrites its range while decode goes on
+        with torch.cuda.stream(copy_stream):
+            c.pool_t.view(g.num_blocks, g.block_elems)[lo:hi] = synth.BF16_NAN_BITS
+        copy_stream.synchronize()
+        time.sleep(0.02)
+        stop.set()
+        th.join(timeout=60)
+        assert not th.is_alive() and result["error"] is None, result["error"]
+        assert result["bad"] == 0 and result["passes"] >= 3
+        assert stats.n_chunks >= 16 and stats.host_seconds >= (stats.bytes_moved - (1 << 20)) / cap
+        assert orc.reclaim(lo, hi)[0] == R.OK
+        compare_state(c, orc, [(lo, hi)])
+        vkv.kv_attn_check(c.pool, c.ws)
+        print(f"{passes_during} decode passes finished while {stats.bytes_moved / 1e6:.1f} MB moved in "
+              f"{stats.host_seconds * 1e3:.1f} ms; {result['passes']} passes in all, all bit-identical", flush=True)
+    finally:
+        c.close()

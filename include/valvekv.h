@@ -247,6 +247,78 @@ int kv_reclaim_range(vkv_pool* pool, int32_t lo_block, int32_t hi_block,
 int block_table_rewrite(int32_t* tables_dev, int64_t n_entries, const int32_t* remap_dev,
                         int32_t num_blocks, void* stream);
 
+/* ---- policies (host only) ---------------------------------------------------- */
+
+/* Selective handle reclamation (Algorithm 1, Section 5).  Handle h is blocks
+ * [h*blocks_per_handle, (h+1)*blocks_per_handle).  Reqs(h) = rows of
+ * tables_host (int32 [n_rows][max_blk], -1 = empty) with an entry in h;
+ * Cost(r) = cost_host[r] (the tokens request r would have to recompute).
+ * k times, among handles not yet handed over and not yet chosen, picks the one
+ * whose not-yet-evicted requests cost least in total (ties: lowest handle),
+ * then counts those requests as evicted.  handles_out[k] in pick order;
+ * evicted_rows_out (room for n_rows, ascending) and the counts may be NULL.
+ * Changes nothing in the pool.  Errors: VKV_E_INVAL, VKV_E_NOSPACE (k too large). */
+int kv_select_handles(vkv_pool* pool, const int32_t* tables_host, int32_t n_rows, int32_t max_blk,
+                      const int64_t* cost_host, int32_t k, int32_t* handles_out,
+                      int32_t* evicted_rows_out, int32_t* n_evicted_out, int64_t* total_cost_out);
+
+/* Hands the given handles to the online tenant WITHOUT saving their contents
+ * (the paper's way, Section 5: the fallback of this library when relocation
+ * finds no room): their blocks stop being live, each handle becomes a
+ * handed-over range [h*bph, (h+1)*bph), and every table entry that named one of
+ * their blocks is reported as (row, column, block id) in row-major order: the
+ * invalidated ids the framework needs to requeue the affected requests
+ * (their remaining blocks are the framework's to free).  If more than `cap`
+ * entries are affected, *n_inv_out gets the number needed, VKV_E_NOSPACE is
+ * returned and nothing changes.  Errors: VKV_E_INVAL, VKV_E_BUSY, VKV_E_NOSPACE. */
+int kv_invalidate_handles(vkv_pool* pool, const int32_t* handles_host, int32_t k,
+                          const int32_t* tables_host, int32_t n_rows, int32_t max_blk,
+                          int32_t* inv_row_out, int32_t* inv_col_out, int32_t* inv_block_out,
+                          int32_t cap, int32_t* n_inv_out);
+
+/* Dynamic reservation (Section 5, "Dynamic MIAD-style memory reservation"): the
+ * online tenant's headroom H, in handles.  The paper fixes only the 90 %
+ * threshold; every other constant is a parameter. */
+typedef struct vkv_miad_config {
+  int32_t h_init, h_min, h_max; /* headroom bounds, handles */
+  int32_t reserved;
+  double  alpha;                /* > 1: H <- ceil(H * alpha) on a pressure event (at least +1) */
+  double  pressure_frac;        /* pressure event when used >= pressure_frac * H; the paper: 0.9 */
+  double  t_init, t_min, t_max; /* release interval T, seconds */
+  double  t_up;                 /* > 1: T <- T * t_up while the event rate exceeds the target */
+  double  t_down;               /* T <- T - t_down otherwise */
+  double  window_s;             /* sliding window of the event rate */
+  double  target_rate;          /* pressure events per second the user accepts */
+} vkv_miad_config;
+typedef struct vkv_miad vkv_miad;
+typedef struct vkv_miad_step {
+  int32_t headroom;             /* H after this observation */
+  int32_t grow_by;              /* handles to reclaim from the offline tenant now */
+  int32_t release;              /* 1: one handle goes back to the offline tenant */
+  int32_t pressure_event;
+  double  interval_s;           /* T after this observation */
+} vkv_miad_step;
+int kv_miad_init(const vkv_miad_config* cfg, vkv_miad** out);
+int kv_miad_destroy(vkv_miad* m);
+/* One observation: at time now_s (non-decreasing) the online tenant uses
+ * used_handles of its headroom.  Pressure: H grows, the event enters the window,
+ * T adapts.  Otherwise, once T has passed since the last release tick or
+ * event: H shrinks by one if it stays above h_min and above the usage, T adapts. */
+int kv_miad_observe(vkv_miad* m, double now_s, int32_t used_handles, vkv_miad_step* out);
+
+/* Wake-up gate (Section 4.2): offline work is preempted the moment the online
+ * tenant turns busy and may run again only after the online tenant has been idle
+ * for T_cool = 2 G without interruption; G is the largest idle gap seen between
+ * two busy periods of the same request (gaps between decode iterations),
+ * starting from initial_gap_s. */
+typedef struct vkv_gate vkv_gate;
+int kv_gate_init(double initial_gap_s, vkv_gate** out);
+int kv_gate_destroy(vkv_gate* g);
+int kv_gate_online_busy(vkv_gate* g, double now_s, int64_t request_id); /* 1: preempt offline now; 0: already off */
+int kv_gate_online_idle(vkv_gate* g, double now_s);
+int kv_gate_poll(vkv_gate* g, double now_s);                            /* 1: offline may run */
+int kv_gate_stats(vkv_gate* g, double* max_gap_s_out, int64_t* preemptions_out);
+
 /* ---- per-launch timing ---------------------------------------------------- */
 
 #define VKV_PROF_SLICE    0   /* paged_decode_attn_slice kernel; index = slice */

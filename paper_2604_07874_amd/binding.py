@@ -21,6 +21,9 @@ __all__ = [
     "kv_yield_request", "kv_yield_clear", "kv_yield_pending", "kv_reclaim_plan", "kv_reclaim_range",
     "block_table_rewrite", "kv_profile_enable", "kv_profile_read", "ProfileRecord",
     "VKV_PROF_SLICE", "VKV_PROF_RELOCATE", "VKV_PROF_REWRITE",
+    "kv_select_handles", "kv_invalidate_handles", "MiadConfig", "MiadStep", "kv_miad_init", "kv_miad_destroy",
+    "kv_miad_observe", "kv_gate_init", "kv_gate_destroy", "kv_gate_online_busy", "kv_gate_online_idle",
+    "kv_gate_poll", "kv_gate_stats",
 ]
 
 VKV_OK, VKV_YIELDED = 0, 1
@@ -62,6 +65,18 @@ class ProfileRecord(C.Structure):
     _fields_ = [("kind", C.c_int32), ("index", C.c_int32), ("ms", C.c_float)]
 
 
+class MiadConfig(C.Structure):
+    _fields_ = [("h_init", C.c_int32), ("h_min", C.c_int32), ("h_max", C.c_int32), ("reserved", C.c_int32),
+                ("alpha", C.c_double), ("pressure_frac", C.c_double), ("t_init", C.c_double), ("t_min", C.c_double),
+                ("t_max", C.c_double), ("t_up", C.c_double), ("t_down", C.c_double), ("window_s", C.c_double),
+                ("target_rate", C.c_double)]
+
+
+class MiadStep(C.Structure):
+    _fields_ = [("headroom", C.c_int32), ("grow_by", C.c_int32), ("release", C.c_int32),
+                ("pressure_event", C.c_int32), ("interval_s", C.c_double)]
+
+
 def _load():
     path = library_path()
     if not os.path.exists(path):
@@ -97,6 +112,17 @@ _sigs = {
     "kv_reclaim_range": (C.c_int, [_P, C.c_int32, C.c_int32, _P, C.c_int64, C.c_uint64, C.c_uint64, _P, _P, _P,
                                    C.c_uint32, C.POINTER(ReclaimStats)]),
     "block_table_rewrite": (C.c_int, [_P, C.c_int64, _P, C.c_int32, _P]),
+    "kv_select_handles": (C.c_int, [_P, _P, C.c_int32, C.c_int32, _P, C.c_int32, _P, _P, _I32P, C.POINTER(C.c_int64)]),
+    "kv_invalidate_handles": (C.c_int, [_P, _P, C.c_int32, _P, C.c_int32, C.c_int32, _P, _P, _P, C.c_int32, _I32P]),
+    "kv_miad_init": (C.c_int, [C.POINTER(MiadConfig), C.POINTER(_P)]),
+    "kv_miad_destroy": (C.c_int, [_P]),
+    "kv_miad_observe": (C.c_int, [_P, C.c_double, C.c_int32, C.POINTER(MiadStep)]),
+    "kv_gate_init": (C.c_int, [C.c_double, C.POINTER(_P)]),
+    "kv_gate_destroy": (C.c_int, [_P]),
+    "kv_gate_online_busy": (C.c_int, [_P, C.c_double, C.c_int64]),
+    "kv_gate_online_idle": (C.c_int, [_P, C.c_double]),
+    "kv_gate_poll": (C.c_int, [_P, C.c_double]),
+    "kv_gate_stats": (C.c_int, [_P, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
     "kv_profile_enable": (C.c_int, [_P, C.c_int32]),
     "kv_profile_read": (C.c_int, [_P, _P, C.c_int32, _I32P]),
 }
@@ -279,3 +305,78 @@ def kv_profile_read(pool, cap: int) -> np.ndarray:
     n = C.c_int32(0)
     _check(lib.kv_profile_read(pool, buf.ctypes.data, cap, C.byref(n)))
     return buf[:n.value]
+
+
+# ---- policies (host only) ---------------------------------------------------------
+def kv_select_handles(pool, tables_host, cost_host, k: int):
+    """Algorithm 1.  Returns (handles int32[k] in pick order, evicted rows int32[], total cost)."""
+    t = _host(tables_host, np.int32)
+    n_rows, max_blk = t.shape
+    cost = _host(cost_host, np.int64)
+    assert len(cost) == n_rows
+    handles = np.empty(k, dtype=np.int32)
+    ev = np.empty(n_rows, dtype=np.int32)
+    n_ev = C.c_int32(0)
+    total = C.c_int64(0)
+    _check(lib.kv_select_handles(pool, t.ctypes.data, n_rows, max_blk, cost.ctypes.data, k, handles.ctypes.data,
+                                 ev.ctypes.data, C.byref(n_ev), C.byref(total)))
+    return handles, ev[:n_ev.value].copy(), total.value
+
+
+def kv_invalidate_handles(pool, handles, tables_host, cap=None):
+    """Returns (rows, columns, block ids) of the invalidated table entries, row-major order."""
+    t = _host(tables_host, np.int32)
+    n_rows, max_blk = t.shape
+    h = _host(handles, np.int32)
+    cap = t.size if cap is None else cap
+    rows, cols, blks = (np.empty(cap, dtype=np.int32) for _ in range(3))
+    n = C.c_int32(0)
+    _check(lib.kv_invalidate_handles(pool, h.ctypes.data, len(h), t.ctypes.data, n_rows, max_blk, rows.ctypes.data,
+                                     cols.ctypes.data, blks.ctypes.data, cap, C.byref(n)))
+    return rows[:n.value].copy(), cols[:n.value].copy(), blks[:n.value].copy()
+
+
+def kv_miad_init(**kw):
+    cfg = MiadConfig(reserved=0, **kw)
+    out = _P()
+    _check(lib.kv_miad_init(C.byref(cfg), C.byref(out)))
+    return out
+
+
+def kv_miad_destroy(m):
+    _check(lib.kv_miad_destroy(m))
+
+
+def kv_miad_observe(m, now_s: float, used_handles: int):
+    """Returns (headroom, grow_by, release, pressure_event, interval_s)."""
+    st = MiadStep()
+    _check(lib.kv_miad_observe(m, now_s, used_handles, C.byref(st)))
+    return st.headroom, st.grow_by, st.release, st.pressure_event, st.interval_s
+
+
+def kv_gate_init(initial_gap_s: float):
+    out = _P()
+    _check(lib.kv_gate_init(initial_gap_s, C.byref(out)))
+    return out
+
+
+def kv_gate_destroy(g):
+    _check(lib.kv_gate_destroy(g))
+
+
+def kv_gate_online_busy(g, now_s: float, request_id: int) -> int:
+    return _check(lib.kv_gate_online_busy(g, now_s, request_id), ok=(0, 1))
+
+
+def kv_gate_online_idle(g, now_s: float):
+    _check(lib.kv_gate_online_idle(g, now_s))
+
+
+def kv_gate_poll(g, now_s: float) -> int:
+    return _check(lib.kv_gate_poll(g, now_s), ok=(0, 1))
+
+
+def kv_gate_stats(g):
+    gap, n = C.c_double(0), C.c_int64(0)
+    _check(lib.kv_gate_stats(g, C.byref(gap), C.byref(n)))
+    return gap.value, n.value

@@ -1,0 +1,256 @@
+// Host-side policies of the paper that steer the hot path: which handles to give up when
+// relocation cannot fit (Algorithm 1, Section 5), how much headroom to keep for the online
+// tenant (MIAD reservation, Section 5), and when offline work may wake up again
+// (cooldown T_cool = 2G, Section 4.2).  No device work.
+#include "vkv_internal.h"
+
+#include <algorithm>
+#include <cmath>
+#include <deque>
+
+using namespace vkv;
+
+struct vkv_miad {
+  vkv_miad_config c;
+  int32_t h;
+  double t;
+  std::deque<double> events;
+  bool started = false;
+  double last_release = 0.0;
+};
+
+struct vkv_gate {
+  double g;
+  bool busy = false;
+  double idle_since = 0.0;
+  bool offline_on = true;
+  bool has_last = false;
+  int64_t last_request = 0;
+  int64_t preemptions = 0;
+};
+
+// Reqs(h) as sorted, duplicate-free row lists
+static void handle_rows(const vkv_pool* p, const int32_t* tables, int32_t n_rows, int32_t max_blk,
+                        std::vector<std::vector<int32_t>>& reqs) {
+  const int32_t bph = p->cfg.blocks_per_handle, nb = p->cfg.num_blocks;
+  reqs.assign((size_t)(nb / bph), {});
+  for (int32_t r = 0; r < n_rows; ++r)
+    for (int32_t j = 0; j < max_blk; ++j) {
+      const int32_t e = tables[(size_t)r * max_blk + j];
+      if (e < 0 || e >= nb) continue;
+      auto& v = reqs[(size_t)(e / bph)];
+      if (v.empty() || v.back() != r) v.push_back(r);   // rows are visited in ascending order
+    }
+}
+
+extern "C" {
+
+int kv_select_handles(vkv_pool* p, const int32_t* tables, int32_t n_rows, int32_t max_blk, const int64_t* cost,
+                      int32_t k, int32_t* handles_out, int32_t* evicted_rows_out, int32_t* n_evicted_out,
+                      int64_t* total_cost_out) {
+  if (!p || n_rows < 0 || max_blk < 0 || (n_rows > 0 && max_blk > 0 && !tables) || (n_rows > 0 && !cost) || k < 0 ||
+      (k > 0 && !handles_out)) {
+    set_error("kv_select_handles: bad argument");
+    return VKV_E_INVAL;
+  }
+  const int32_t bph = p->cfg.blocks_per_handle, n_handles = p->cfg.num_blocks / bph;
+  std::vector<std::vector<int32_t>> reqs;
+  handle_rows(p, tables, n_rows, max_blk, reqs);
+  std::vector<uint8_t> candidate((size_t)n_handles, 1), evicted((size_t)n_rows, 0);
+  int32_t n_cand = 0;
+  for (int32_t h = 0; h < n_handles; ++h) {
+    if (in_released(p, h * bph)) candidate[(size_t)h] = 0;   // already with the online tenant
+    n_cand += candidate[(size_t)h];
+  }
+  if (k > n_cand) {
+    set_error("kv_select_handles: %d handles wanted, %d not yet handed over", k, n_cand);
+    return VKV_E_NOSPACE;
+  }
+  int64_t total = 0;
+  for (int32_t i = 0; i < k; ++i) {
+    int32_t best = -1;
+    int64_t best_cost = 0;
+    for (int32_t h = 0; h < n_handles; ++h) {
+      if (!candidate[(size_t)h]) continue;
+      int64_t c = 0;
+      for (int32_t r : reqs[(size_t)h])
+        if (!evicted[(size_t)r]) c += cost[r];
+      if (best < 0 || c < best_cost) { best = h; best_cost = c; }   // ties: lowest handle index
+    }
+    handles_out[i] = best;
+    candidate[(size_t)best] = 0;
+    total += best_cost;
+    for (int32_t r : reqs[(size_t)best]) evicted[(size_t)r] = 1;
+  }
+  int32_t n_ev = 0;
+  for (int32_t r = 0; r < n_rows; ++r)
+    if (evicted[(size_t)r]) {
+      if (evicted_rows_out) evicted_rows_out[n_ev] = r;
+      ++n_ev;
+    }
+  if (n_evicted_out) *n_evicted_out = n_ev;
+  if (total_cost_out) *total_cost_out = total;
+  return VKV_OK;
+}
+
+int kv_invalidate_handles(vkv_pool* p, const int32_t* handles, int32_t k, const int32_t* tables, int32_t n_rows,
+                          int32_t max_blk, int32_t* inv_row_out, int32_t* inv_col_out, int32_t* inv_block_out,
+                          int32_t cap, int32_t* n_inv_out) {
+  if (!p || k < 0 || (k > 0 && !handles) || n_rows < 0 || max_blk < 0 || (n_rows > 0 && max_blk > 0 && !tables) ||
+      cap < 0 || !n_inv_out) {
+    set_error("kv_invalidate_handles: bad argument");
+    return VKV_E_INVAL;
+  }
+  const int32_t bph = p->cfg.blocks_per_handle, n_handles = p->cfg.num_blocks / bph;
+  std::vector<uint8_t> chosen((size_t)n_handles, 0);
+  for (int32_t i = 0; i < k; ++i) {
+    const int32_t h = handles[i];
+    if (h < 0 || h >= n_handles || chosen[(size_t)h]) { set_error("kv_invalidate_handles: bad or repeated handle %d", h); return VKV_E_INVAL; }
+    if (in_released(p, h * bph)) { set_error("kv_invalidate_handles: handle %d is already handed over", h); return VKV_E_BUSY; }
+    chosen[(size_t)h] = 1;
+  }
+  // count first, so that a too small output leaves everything untouched
+  int64_t n_inv = 0;
+  for (int32_t r = 0; r < n_rows; ++r)
+    for (int32_t j = 0; j < max_blk; ++j) {
+      const int32_t e = tables[(size_t)r * max_blk + j];
+      if (e >= 0 && e < p->cfg.num_blocks && chosen[(size_t)(e / bph)]) ++n_inv;
+    }
+  if (n_inv > cap) {
+    *n_inv_out = (int32_t)std::min<int64_t>(n_inv, 0x7FFFFFFF);
+    set_error("kv_invalidate_handles: %lld invalidated entries, room for %d", (long long)n_inv, cap);
+    return VKV_E_NOSPACE;
+  }
+  int32_t w = 0;
+  for (int32_t r = 0; r < n_rows; ++r)
+    for (int32_t j = 0; j < max_blk; ++j) {
+      const int32_t e = tables[(size_t)r * max_blk + j];
+      if (e >= 0 && e < p->cfg.num_blocks && chosen[(size_t)(e / bph)]) {
+        if (inv_row_out) inv_row_out[w] = r;
+        if (inv_col_out) inv_col_out[w] = j;
+        if (inv_block_out) inv_block_out[w] = e;
+        ++w;
+      }
+    }
+  *n_inv_out = w;
+  for (int32_t h = 0; h < n_handles; ++h) {
+    if (!chosen[(size_t)h]) continue;
+    for (int32_t b = h * bph; b < (h + 1) * bph; ++b)
+      if (p->live[(size_t)b]) { p->live[(size_t)b] = 0; --p->n_live; }
+    p->released.emplace_back(h * bph, (h + 1) * bph);
+  }
+  return VKV_OK;
+}
+
+// ---- MIAD headroom ----------------------------------------------------------------------
+
+int kv_miad_init(const vkv_miad_config* c, vkv_miad** out) {
+  if (!c || !out) { set_error("kv_miad_init: null argument"); return VKV_E_INVAL; }
+  *out = nullptr;
+  if (c->h_min < 1 || c->h_init < c->h_min || c->h_max < c->h_init || !(c->alpha > 1.0) ||
+      !(c->pressure_frac > 0.0 && c->pressure_frac <= 1.0) || !(c->t_min > 0.0) || c->t_init < c->t_min ||
+      c->t_max < c->t_init || !(c->t_up > 1.0) || c->t_down < 0.0 || !(c->window_s > 0.0) || c->target_rate < 0.0) {
+    set_error("kv_miad_init: inconsistent configuration");
+    return VKV_E_INVAL;
+  }
+  vkv_miad* m = new vkv_miad();
+  m->c = *c;
+  m->h = c->h_init;
+  m->t = c->t_init;
+  *out = m;
+  return VKV_OK;
+}
+
+int kv_miad_destroy(vkv_miad* m) {
+  delete m;
+  return VKV_OK;
+}
+
+static void adapt_interval(vkv_miad* m, double now) {
+  while (!m->events.empty() && !(m->events.front() > now - m->c.window_s)) m->events.pop_front();
+  const double rate = (double)m->events.size() / m->c.window_s;
+  if (rate > m->c.target_rate) m->t = std::min(m->c.t_max, m->t * m->c.t_up);
+  else m->t = std::max(m->c.t_min, m->t - m->c.t_down);
+}
+
+int kv_miad_observe(vkv_miad* m, double now_s, int32_t used_handles, vkv_miad_step* out) {
+  if (!m || !out || used_handles < 0) { set_error("kv_miad_observe: bad argument"); return VKV_E_INVAL; }
+  if (!m->started) { m->started = true; m->last_release = now_s; }
+  *out = vkv_miad_step{};
+  if ((double)used_handles >= m->c.pressure_frac * (double)m->h) {
+    out->pressure_event = 1;
+    const int32_t grown = (int32_t)std::ceil((double)m->h * m->c.alpha);
+    const int32_t new_h = std::min(m->c.h_max, std::max(m->h + 1, grown));
+    out->grow_by = new_h - m->h;
+    m->h = new_h;
+    m->events.push_back(now_s);
+    adapt_interval(m, now_s);
+    m->last_release = now_s;
+  } else if (now_s - m->last_release >= m->t) {
+    if (m->h > m->c.h_min && m->h - 1 > used_handles) {
+      --m->h;
+      out->release = 1;
+    }
+    m->last_release = now_s;
+    adapt_interval(m, now_s);
+  }
+  out->headroom = m->h;
+  out->interval_s = m->t;
+  return VKV_OK;
+}
+
+// ---- cooldown gate ---------------------------------------------------------------------
+
+int kv_gate_init(double initial_gap_s, vkv_gate** out) {
+  if (!out || !(initial_gap_s >= 0.0)) { set_error("kv_gate_init: bad argument"); return VKV_E_INVAL; }
+  vkv_gate* g = new vkv_gate();
+  g->g = initial_gap_s;
+  *out = g;
+  return VKV_OK;
+}
+
+int kv_gate_destroy(vkv_gate* g) {
+  delete g;
+  return VKV_OK;
+}
+
+int kv_gate_online_busy(vkv_gate* g, double now_s, int64_t request_id) {
+  if (!g) return VKV_E_INVAL;
+  int preempt = 0;
+  if (!g->busy) {
+    if (g->has_last && request_id == g->last_request) g->g = std::max(g->g, now_s - g->idle_since);
+    g->busy = true;
+  }
+  if (g->offline_on) {
+    g->offline_on = false;
+    ++g->preemptions;
+    preempt = 1;
+  }
+  g->has_last = true;
+  g->last_request = request_id;
+  return preempt;
+}
+
+int kv_gate_online_idle(vkv_gate* g, double now_s) {
+  if (!g) return VKV_E_INVAL;
+  if (g->busy) {
+    g->busy = false;
+    g->idle_since = now_s;
+  }
+  return VKV_OK;
+}
+
+int kv_gate_poll(vkv_gate* g, double now_s) {
+  if (!g) return VKV_E_INVAL;
+  if (!g->offline_on && !g->busy && now_s - g->idle_since >= 2.0 * g->g) g->offline_on = true;
+  return g->offline_on ? 1 : 0;
+}
+
+int kv_gate_stats(vkv_gate* g, double* max_gap_s_out, int64_t* preemptions_out) {
+  if (!g) return VKV_E_INVAL;
+  if (max_gap_s_out) *max_gap_s_out = g->g;
+  if (preemptions_out) *preemptions_out = g->preemptions;
+  return VKV_OK;
+}
+
+}  // extern "C"

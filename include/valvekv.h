@@ -247,6 +247,67 @@ int kv_reclaim_range(vkv_pool* pool, int32_t lo_block, int32_t hi_block,
 int block_table_rewrite(int32_t* tables_dev, int64_t n_entries, const int32_t* remap_dev,
                         int32_t num_blocks, void* stream);
 
+/* ---- prefill attention (head_dim 128) ------------------------------------------- */
+
+typedef struct vkv_prefill_plan_info {
+  int32_t  n_items, n_slices, n_tiles;
+  int32_t  tile_positions;      /* query positions per tile = 128 / (G rounded up to a power of two) */
+  int32_t  total_q;             /* sum of q_len: rows of q and out */
+  int32_t  reserved;
+  uint64_t workspace_bytes;
+  uint64_t kv_bytes_per_layer;  /* K+V bytes all items read (tokens are re-read once per query tile) */
+  uint64_t max_slice_kv_bytes;
+  double   flops_per_layer;     /* 4 * D * Hq * sum over queries of (position + 1): the causal attention itself */
+} vkv_prefill_plan_info;
+
+/* Host only.  Plans the causal attention of the newest q_len_host[s] tokens of
+ * every sequence (positions ctx_len[s] - q_len[s] .. ctx_len[s] - 1; their K/V is
+ * already in the cache) as preemptible slices: long prefills are where the
+ * paper finds coarse preemption costliest (Section 2.2, Section 5).
+ *   - the new tokens of a sequence are cut into tiles of tile_positions positions;
+ *   - the tokens a tile can see (0 .. its last position) are cut into chunks of
+ *     chunk_tokens (multiple of 32 in [32, 2048]);
+ *   - work item = (tile, kv head, chunk), order tile, chunk, kv head;
+ *   - a slice is a maximal run of items reading at most slice_bytes of K+V.
+ * Query rows are packed: sequence s owns rows sum(q_len[:s]) .. + q_len[s].
+ * Errors: VKV_E_INVAL (needs 1 <= q_len <= ctx_len). */
+int kv_prefill_plan(vkv_pool* pool, const int32_t* ctx_len_host, const int32_t* q_len_host, int32_t num_seqs,
+                    uint64_t slice_bytes, int32_t chunk_tokens, vkv_prefill_plan_info* info_out);
+
+/* work_out_host[n_items][4] = (tile, kv_head, first_block_index, n_tokens);
+ * slice_start_out_host[n_slices+1]; tiles_out_host[n_tiles][4] = (sequence, first q
+ * row, first position, positions); tile_base_out_host[n_tiles+1].  Any may be NULL. */
+int kv_prefill_plan_read(vkv_pool* pool, int32_t* work_out_host, int32_t* slice_start_out_host,
+                         int32_t* tiles_out_host, int32_t* tile_base_out_host);
+
+/* As kv_attn_bind, for the prefill plan (its own workspace). */
+int kv_prefill_bind(vkv_pool* pool, void* workspace, uint64_t workspace_bytes, void* stream);
+
+/* Enqueues one slice: for every work item, causal scores q.k/sqrt(D) (or
+ * * softmax_scale) of the tile's (position, query head) columns against the
+ * item's tokens, running max / sum / weighted V sum per column; a token at
+ * position t is visible to the query at position p iff t <= p.  Items that cover
+ * everything their tile can see write out directly; the others leave partial
+ * results in the workspace for kv_prefill_merge.
+ *   q_bf16   device [total_q][num_q_heads][128]
+ *   out_f32  device fp32 [total_q][num_q_heads][128], 16-byte aligned */
+int paged_prefill_attn_slice(vkv_pool* pool, int32_t layer, int32_t slice,
+                             const void* q_bf16, const int32_t* block_table, int32_t max_blk,
+                             void* workspace, void* out_f32, float softmax_scale, void* stream);
+
+/* Enqueues the merge of split tiles (log-sum-exp, chunk order) into out; call
+ * after every slice of the layer has been enqueued on the same stream. */
+int kv_prefill_merge(vkv_pool* pool, void* workspace, void* out_f32, void* stream);
+
+/* Slice scheduler for prefill: as kv_attn_run_layer, followed by the merge. */
+int kv_prefill_run_layer(vkv_pool* pool, int32_t layer, int32_t* cursor_slice,
+                         const void* q_bf16, const int32_t* block_table, int32_t max_blk,
+                         void* workspace, void* out_f32, float softmax_scale,
+                         int32_t max_inflight, void* stream);
+
+/* As kv_attn_check. */
+int kv_prefill_check(vkv_pool* pool, void* workspace, void* stream);
+
 /* ---- policies (host only) ---------------------------------------------------- */
 
 /* Selective handle reclamation (Algorithm 1, Section 5).  Handle h is blocks
@@ -325,6 +386,8 @@ int kv_gate_stats(vkv_gate* g, double* max_gap_s_out, int64_t* preemptions_out);
 #define VKV_PROF_RELOCATE 1   /* all block copy launches of one kv_reclaim_range call;
                                  index = number of launches */
 #define VKV_PROF_REWRITE  2   /* table rewrite kernel */
+#define VKV_PROF_PREFILL  3   /* paged_prefill_attn_slice kernel; index = slice */
+#define VKV_PROF_PREFILL_MERGE 4
 
 typedef struct vkv_profile_record {
   int32_t kind;

@@ -47,3 +47,54 @@ def attention_plan(ctx_len, num_kv_heads: int, head_dim: int, block_tokens: int,
     starts.append(len(work))
     return (np.asarray(work, dtype=np.int32).reshape(-1, 4),
             np.asarray(starts, dtype=np.int32))
+
+
+def prefill_plan(ctx_len, q_len, num_q_heads: int, num_kv_heads: int, head_dim: int, block_tokens: int,
+                 chunk_tokens: int, slice_bytes: int):
+    """Work split of a causal prefill step (the newest q_len[s] tokens of every sequence).
+
+    tile  = up to 128 // GP consecutive new positions of one sequence (GP = query heads per kv
+            head, rounded up to a power of two): (sequence, first q row, first position, positions);
+            q rows are packed sequence after sequence.
+    item  = (tile, kv_head, first_block_index, n_tokens): a chunk of at most chunk_tokens of the
+            tokens the tile can see (0 .. its last position); order tile, chunk, kv head.
+    slice = maximal run of items with at most slice_bytes of K+V (at least one item).
+    Returns (work [n_items,4], slice_start, tiles [n_tiles,4], tile_base [n_tiles+1]).
+    """
+    if chunk_tokens <= 0 or chunk_tokens % 32:
+        raise ValueError("chunk_tokens must be a positive multiple of 32")
+    group = num_q_heads // num_kv_heads
+    gp = 1
+    while gp < group:
+        gp *= 2
+    qp = 128 // gp
+    work, tiles, tile_base = [], [], []
+    row = 0
+    for s, (n, ql) in enumerate(zip((int(v) for v in ctx_len), (int(v) for v in q_len))):
+        if ql < 1 or n < ql:
+            raise ValueError("need 1 <= q_len <= context length")
+        t = 0
+        while t * qp < ql:
+            n_pos = min(qp, ql - t * qp)
+            pos0 = n - ql + t * qp
+            tile_base.append(len(work))
+            tiles.append((s, row + t * qp, pos0, n_pos))
+            visible, first = pos0 + n_pos, 0
+            while first < visible:
+                for h in range(num_kv_heads):
+                    work.append((len(tiles) - 1, h, first // block_tokens, min(chunk_tokens, visible - first)))
+                first += chunk_tokens
+            t += 1
+        row += ql
+    tile_base.append(len(work))
+    token_bytes = 2 * head_dim * 2
+    starts, acc = [0], 0
+    for i, w in enumerate(work):
+        b = w[3] * token_bytes
+        if i > starts[-1] and acc + b > slice_bytes:
+            starts.append(i)
+            acc = 0
+        acc += b
+    starts.append(len(work))
+    return (np.asarray(work, dtype=np.int32).reshape(-1, 4), np.asarray(starts, dtype=np.int32),
+            np.asarray(tiles, dtype=np.int32).reshape(-1, 4), np.asarray(tile_base, dtype=np.int32))

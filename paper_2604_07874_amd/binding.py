@@ -21,6 +21,8 @@ __all__ = [
     "kv_yield_request", "kv_yield_clear", "kv_yield_pending", "kv_reclaim_plan", "kv_reclaim_range",
     "block_table_rewrite", "kv_profile_enable", "kv_profile_read", "ProfileRecord",
     "VKV_PROF_SLICE", "VKV_PROF_RELOCATE", "VKV_PROF_REWRITE",
+    "PrefillPlanInfo", "kv_prefill_plan", "kv_prefill_plan_read", "kv_prefill_bind", "paged_prefill_attn_slice",
+    "kv_prefill_merge", "kv_prefill_run_layer", "kv_prefill_check", "VKV_PROF_PREFILL", "VKV_PROF_PREFILL_MERGE",
     "kv_select_handles", "kv_invalidate_handles", "MiadConfig", "MiadStep", "kv_miad_init", "kv_miad_destroy",
     "kv_miad_observe", "kv_gate_init", "kv_gate_destroy", "kv_gate_online_busy", "kv_gate_online_idle",
     "kv_gate_poll", "kv_gate_stats",
@@ -29,7 +31,7 @@ __all__ = [
 VKV_OK, VKV_YIELDED = 0, 1
 VKV_E_INVAL, VKV_E_NOSPACE, VKV_E_BUSY, VKV_E_HIP, VKV_E_STATE = -1, -2, -3, -4, -5
 VKV_RECLAIM_ASYNC = 1
-VKV_PROF_SLICE, VKV_PROF_RELOCATE, VKV_PROF_REWRITE = 0, 1, 2
+VKV_PROF_SLICE, VKV_PROF_RELOCATE, VKV_PROF_REWRITE, VKV_PROF_PREFILL, VKV_PROF_PREFILL_MERGE = 0, 1, 2, 3, 4
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
@@ -63,6 +65,13 @@ class ReclaimStats(C.Structure):
 
 class ProfileRecord(C.Structure):
     _fields_ = [("kind", C.c_int32), ("index", C.c_int32), ("ms", C.c_float)]
+
+
+class PrefillPlanInfo(C.Structure):
+    _fields_ = [("n_items", C.c_int32), ("n_slices", C.c_int32), ("n_tiles", C.c_int32),
+                ("tile_positions", C.c_int32), ("total_q", C.c_int32), ("reserved", C.c_int32),
+                ("workspace_bytes", C.c_uint64), ("kv_bytes_per_layer", C.c_uint64),
+                ("max_slice_kv_bytes", C.c_uint64), ("flops_per_layer", C.c_double)]
 
 
 class MiadConfig(C.Structure):
@@ -112,6 +121,13 @@ _sigs = {
     "kv_reclaim_range": (C.c_int, [_P, C.c_int32, C.c_int32, _P, C.c_int64, C.c_uint64, C.c_uint64, _P, _P, _P,
                                    C.c_uint32, C.POINTER(ReclaimStats)]),
     "block_table_rewrite": (C.c_int, [_P, C.c_int64, _P, C.c_int32, _P]),
+    "kv_prefill_plan": (C.c_int, [_P, _P, _P, C.c_int32, C.c_uint64, C.c_int32, C.POINTER(PrefillPlanInfo)]),
+    "kv_prefill_plan_read": (C.c_int, [_P, _P, _P, _P, _P]),
+    "kv_prefill_bind": (C.c_int, [_P, _P, C.c_uint64, _P]),
+    "paged_prefill_attn_slice": (C.c_int, [_P, C.c_int32, C.c_int32, _P, _P, C.c_int32, _P, _P, C.c_float, _P]),
+    "kv_prefill_merge": (C.c_int, [_P, _P, _P, _P]),
+    "kv_prefill_run_layer": (C.c_int, [_P, C.c_int32, _I32P, _P, _P, C.c_int32, _P, _P, C.c_float, C.c_int32, _P]),
+    "kv_prefill_check": (C.c_int, [_P, _P, _P]),
     "kv_select_handles": (C.c_int, [_P, _P, C.c_int32, C.c_int32, _P, C.c_int32, _P, _P, _I32P, C.POINTER(C.c_int64)]),
     "kv_invalidate_handles": (C.c_int, [_P, _P, C.c_int32, _P, C.c_int32, C.c_int32, _P, _P, _P, C.c_int32, _I32P]),
     "kv_miad_init": (C.c_int, [C.POINTER(MiadConfig), C.POINTER(_P)]),
@@ -305,6 +321,53 @@ def kv_profile_read(pool, cap: int) -> np.ndarray:
     n = C.c_int32(0)
     _check(lib.kv_profile_read(pool, buf.ctypes.data, cap, C.byref(n)))
     return buf[:n.value]
+
+
+# ---- prefill ----------------------------------------------------------------------
+def kv_prefill_plan(pool, ctx_len_host, q_len_host, slice_bytes: int, chunk_tokens: int) -> PrefillPlanInfo:
+    ctx = _host(ctx_len_host, np.int32)
+    ql = _host(q_len_host, np.int32)
+    assert len(ctx) == len(ql)
+    info = PrefillPlanInfo()
+    _check(lib.kv_prefill_plan(pool, ctx.ctypes.data, ql.ctypes.data, len(ctx), slice_bytes, chunk_tokens, C.byref(info)))
+    return info
+
+
+def kv_prefill_plan_read(pool, info: PrefillPlanInfo):
+    """Returns (work [n_items,4], slice_start [n_slices+1], tiles [n_tiles,4], tile_base [n_tiles+1])."""
+    work = np.empty((info.n_items, 4), dtype=np.int32)
+    starts = np.empty(info.n_slices + 1, dtype=np.int32)
+    tiles = np.empty((info.n_tiles, 4), dtype=np.int32)
+    tile_base = np.empty(info.n_tiles + 1, dtype=np.int32)
+    _check(lib.kv_prefill_plan_read(pool, work.ctypes.data, starts.ctypes.data, tiles.ctypes.data, tile_base.ctypes.data))
+    return work, starts, tiles, tile_base
+
+
+def kv_prefill_bind(pool, workspace, stream=None):
+    _check(lib.kv_prefill_bind(pool, _dev(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def paged_prefill_attn_slice(pool, layer: int, slice_idx: int, q, block_table, workspace, out,
+                             softmax_scale: float = 0.0, stream=None):
+    _check(lib.paged_prefill_attn_slice(pool, layer, slice_idx, _dev(q), _dev(block_table), block_table.shape[-1],
+                                        _dev(workspace), _dev(out), softmax_scale, _stream(stream)))
+
+
+def kv_prefill_merge(pool, workspace, out, stream=None):
+    _check(lib.kv_prefill_merge(pool, _dev(workspace), _dev(out), _stream(stream)))
+
+
+def kv_prefill_run_layer(pool, layer: int, cursor: int, q, block_table, workspace, out,
+                         softmax_scale: float = 0.0, max_inflight: int = 2, stream=None):
+    cur = C.c_int32(cursor)
+    st = lib.kv_prefill_run_layer(pool, layer, C.byref(cur), _dev(q), _dev(block_table), block_table.shape[-1],
+                                  _dev(workspace), _dev(out), softmax_scale, max_inflight, _stream(stream))
+    _check(st, ok=(VKV_OK, VKV_YIELDED))
+    return st, cur.value
+
+
+def kv_prefill_check(pool, workspace, stream=None):
+    _check(lib.kv_prefill_check(pool, _dev(workspace), _stream(stream)))
 
 
 # ---- policies (host only) ---------------------------------------------------------

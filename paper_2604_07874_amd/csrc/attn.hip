@@ -35,6 +35,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <functional>
 
 namespace vkv {
 
@@ -406,6 +407,63 @@ static int check_slice_args(vkv_pool* p, int32_t layer, const void* q, const int
   return VKV_OK;
 }
 
+// Slice scheduler shared by decode and prefill: issues slices *cursor .. n_slices-1 through
+// `launch`, then `tail` (if any), keeping at most max_inflight launches unfinished; the ring of
+// events persists across calls.  Stops at a slice boundary when the yield flag is set.
+int run_slices(vkv_pool* p, int32_t* cursor, int32_t n_slices, int32_t max_inflight, hipStream_t hs,
+               const char* who, const std::function<int(int32_t)>& launch, const std::function<int()>& tail) {
+  if (!cursor || *cursor < 0 || *cursor > n_slices || max_inflight < 1 || max_inflight > kMaxInflight) {
+    set_error("%s: bad cursor or max_inflight", who);
+    return VKV_E_INVAL;
+  }
+  int st = VKV_OK;
+  for (int i = 0; i < max_inflight; ++i)
+    if (!p->inflight_ev[i]) VKV_HIP(hipEventCreateWithFlags(&p->inflight_ev[i], hipEventDisableTiming));
+  auto drain = [&]() -> int {
+    for (; p->inflight_count > 0; --p->inflight_count, p->inflight_head = (p->inflight_head + 1) % p->inflight_cap)
+      VKV_HIP(hipEventSynchronize(p->inflight_ev[p->inflight_head]));
+    p->inflight_head = 0;
+    return VKV_OK;
+  };
+  if (p->inflight_cap != max_inflight) {
+    st = drain();
+    if (st != VKV_OK) return st;
+    p->inflight_cap = max_inflight;
+  }
+  // one more launch may be enqueued once fewer than max_inflight are unfinished
+  auto admit = [&]() -> int {
+    if (p->inflight_count == max_inflight) {
+      VKV_HIP(hipEventSynchronize(p->inflight_ev[p->inflight_head]));
+      p->inflight_head = (p->inflight_head + 1) % max_inflight;
+      --p->inflight_count;
+    }
+    return VKV_OK;
+  };
+  auto track = [&]() -> int {
+    VKV_HIP(hipEventRecord(p->inflight_ev[(p->inflight_head + p->inflight_count) % max_inflight], hs));
+    ++p->inflight_count;
+    return VKV_OK;
+  };
+  for (int32_t s = *cursor; s < n_slices; ++s) {
+    if (p->yield_flag.load(std::memory_order_acquire)) {
+      st = drain();
+      if (st != VKV_OK) return st;
+      *cursor = s;
+      return VKV_YIELDED;
+    }
+    if ((st = admit()) != VKV_OK) return st;
+    if ((st = launch(s)) != VKV_OK) return st;
+    if ((st = track()) != VKV_OK) return st;
+  }
+  if (tail && *cursor < n_slices + 1) {
+    if ((st = admit()) != VKV_OK) return st;
+    if ((st = tail()) != VKV_OK) return st;
+    if ((st = track()) != VKV_OK) return st;
+  }
+  *cursor = n_slices;
+  return VKV_OK;
+}
+
 }  // namespace vkv
 
 using namespace vkv;
@@ -542,51 +600,10 @@ int kv_attn_run_layer(vkv_pool* p, int32_t layer, int32_t* cursor, const void* q
   int st = check_slice_args(p, layer, q, table, max_blk, workspace, out, "kv_attn_run_layer");
   if (st != VKV_OK) return st;
   const int32_t n_slices = (int32_t)p->slice_start.size() - 1;
-  if (!cursor || *cursor < 0 || *cursor > n_slices || max_inflight < 1 || max_inflight > kMaxInflight) {
-    set_error("kv_attn_run_layer: bad cursor or max_inflight");
-    return VKV_E_INVAL;
-  }
   hipStream_t hs = (hipStream_t)stream;
-  for (int i = 0; i < max_inflight; ++i)
-    if (!p->inflight_ev[i]) VKV_HIP(hipEventCreateWithFlags(&p->inflight_ev[i], hipEventDisableTiming));
-  auto drain = [&]() -> int {
-    for (; p->inflight_count > 0; --p->inflight_count, p->inflight_head = (p->inflight_head + 1) % p->inflight_cap)
-      VKV_HIP(hipEventSynchronize(p->inflight_ev[p->inflight_head]));
-    p->inflight_head = 0;
-    return VKV_OK;
-  };
-  if (p->inflight_cap != max_inflight) {
-    st = drain();
-    if (st != VKV_OK) return st;
-    p->inflight_cap = max_inflight;
-  }
-  // one more launch may be enqueued once fewer than max_inflight are unfinished
-  auto admit = [&]() -> int {
-    if (p->inflight_count == max_inflight) {
-      VKV_HIP(hipEventSynchronize(p->inflight_ev[p->inflight_head]));
-      p->inflight_head = (p->inflight_head + 1) % max_inflight;
-      --p->inflight_count;
-    }
-    return VKV_OK;
-  };
-  auto track = [&]() -> int {
-    VKV_HIP(hipEventRecord(p->inflight_ev[(p->inflight_head + p->inflight_count) % max_inflight], hs));
-    ++p->inflight_count;
-    return VKV_OK;
-  };
-  for (int32_t s = *cursor; s < n_slices; ++s) {
-    if (p->yield_flag.load(std::memory_order_acquire)) {
-      st = drain();
-      if (st != VKV_OK) return st;
-      *cursor = s;
-      return VKV_YIELDED;
-    }
-    if ((st = admit()) != VKV_OK) return st;
-    if ((st = launch_slice(p, layer, s, q, table, max_blk, workspace, out, scale, hs)) != VKV_OK) return st;
-    if ((st = track()) != VKV_OK) return st;
-  }
-  *cursor = n_slices;
-  return VKV_OK;
+  return run_slices(p, cursor, n_slices, max_inflight, hs, "kv_attn_run_layer",
+                    [&](int32_t s) { return launch_slice(p, layer, s, q, table, max_blk, workspace, out, scale, hs); },
+                    nullptr);
 }
 
 }  // extern "C"

@@ -1,0 +1,521 @@
+// Preemptible causal attention of a chunk of new tokens over the paged KV pool (prefill).
+//
+// Long prefills are where coarse preemption costs most (paper Section 2.2: layer-level
+// preemption delays of hundreds of milliseconds at 32k tokens; Section 5: bursts arriving
+// during a long prefill iteration).  The same slicing as for decode bounds the time to the
+// next yield point; here the work is compute-bound, so the MFMA units carry the load.
+//
+// Work split: the new tokens of a sequence are cut into query tiles of 128/GP positions
+// (GP = group size rounded up to a power of two), so a tile has 128 (position, query head)
+// columns; the tokens a tile can see (positions 0 .. its last position) are cut into chunks
+// of chunk_tokens; one work item = (tile, kv head, chunk) = one workgroup.  Items of a tile
+// are merged by a separate small kernel after the layer's last slice (prefill launches last
+// milliseconds, so one more launch per layer is immaterial and needs no in-kernel
+// cross-workgroup ordering).
+//
+// Kernel shape (wave64, gfx950): 4 waves; wave w owns columns [32w, 32w+32) as two 16-column
+// MFMA tiles and sees every token of the item.  Per 32-token group the workgroup stages K and
+// V once for all four waves: wave w loads rows {4r+kg : r in (2(w&1), 2(w&1)+1)} of block
+// w>>1 of the group (K and V, 16 bytes per lane each), writes the K rows to a shared padded
+// LDS tile and one dword (two tokens) of every lane's transposed V operand to a shared LDS
+// array; after a barrier each wave reads the 8 K operands and 8 V operands it needs for its
+// MFMAs (v_mfma_f32_16x16x32_bf16, same operand layouts and token-to-row assignment as the
+// decode kernel) and runs online softmax per column with the causal mask applied by select.
+#include "vkv_internal.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+
+namespace vkv {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kTileColumns = 128;   // (position, query head) columns of one query tile
+constexpr int kNQ = 2;              // 16-column MFMA tiles per wave
+
+struct PrefillParams {
+  const uint16_t* pool;       // pool base + layer offset (elements)
+  const WorkItem* work;       // .seq = tile id
+  const int32_t* tiles;       // [n_tiles][4] = (sequence, first q row, first position, positions)
+  const int32_t* tile_base;   // [n_tiles + 1]
+  const uint16_t* q;          // [total_q][Hq][D]
+  const int32_t* table;
+  float* part_acc;            // [n_items][128][D]
+  float* part_ml;             // [n_items][128][2]
+  float* out;                 // [total_q][Hq][D]
+  uint32_t* err;
+  uint64_t block_elems;
+  uint32_t v_off;
+  int32_t item_first, max_blk, Hq, Hkv, G, gp_shift, NB;
+  float scale_log2;
+};
+
+template <int D>
+__global__ __launch_bounds__(256, 2) void paged_prefill_attn_slice_kernel(const PrefillParams p) {
+  static_assert(D == 128, "head_dim 128 only");
+  constexpr int EPL = D / 16;
+  constexpr int KS = D / 32;
+  constexpr int RS = D * 2 + 16;
+  constexpr float NEG_INF = -INFINITY;
+
+  __shared__ __attribute__((aligned(16))) unsigned char k_lds[32 * RS];
+  __shared__ __attribute__((aligned(16))) uint32_t va_lds[EPL * 64 * 4];
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int c16 = lane & 15, kg = lane >> 4;
+
+  const WorkItem it = p.work[p.item_first + blockIdx.x];
+  const int tile = it.seq;
+  const int seq = p.tiles[4 * tile + 0], row0 = p.tiles[4 * tile + 1], pos0 = p.tiles[4 * tile + 2],
+            n_pos = p.tiles[4 * tile + 3];
+  const int ntok = it.n_tokens;
+  const int tok_base = it.first_block * 16;          // position of the item's first token
+  const int ngroups = (ntok + kGroupTokens - 1) / kGroupTokens;
+  const int G = p.G, gp_mask = (1 << p.gp_shift) - 1;
+
+  // this lane's two columns (one per MFMA tile): position within the tile and query head
+  int cpos[kNQ], cg[kNQ];
+  bool cvalid[kNQ];
+  bf16x8 qb[kNQ][KS];
+#pragma unroll
+  for (int j = 0; j < kNQ; ++j) {
+    const int col = (wave * kNQ + j) * 16 + c16;
+    cpos[j] = col >> p.gp_shift;
+    cg[j] = col & gp_mask;
+    cvalid[j] = cg[j] < G && cpos[j] < n_pos;
+    const uint16_t* qrow = p.q + ((size_t)(row0 + (cvalid[j] ? cpos[j] : 0)) * p.Hq + (size_t)it.kv_head * G +
+                                  (cvalid[j] ? cg[j] : 0)) * D;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (cvalid[j]) v = *reinterpret_cast<const u32x4*>(qrow + ks * 32 + kg * 8);
+      qb[j][ks] = __builtin_bit_cast(bf16x8, v);
+    }
+  }
+
+  const int32_t* trow = p.table + (size_t)seq * p.max_blk + it.first_block;
+  const uint16_t* kplane = p.pool + (size_t)it.kv_head * (16 * D);
+  const int nblk_item = (ntok + 15) >> 4;
+  const int32_t tb0 = lane < nblk_item ? trow[lane] : -1;
+  const int32_t tb1 = 64 + lane < nblk_item ? trow[64 + lane] : -1;
+
+  f32x4 acc[kNQ][EPL];
+  float m_run[kNQ], l_run[kNQ];
+#pragma unroll
+  for (int j = 0; j < kNQ; ++j) {
+    m_run[j] = NEG_INF;
+    l_run[j] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < EPL; ++dt) acc[j][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  // this wave's share of a group: rows 4r+kg, r in {r0, r0+1}, of block (wave >> 1)
+  const int sb = wave >> 1, r0 = (wave & 1) * 2;
+  u32x4 kr[2], vr[2];
+  auto issue = [&](int grp) {
+    const int bi = grp * 2 + sb;
+    const bool have = bi < nblk_item;
+    const int32_t blk = bi < 64 ? __builtin_amdgcn_readlane(tb0, bi & 63) : __builtin_amdgcn_readlane(tb1, bi & 63);
+    if (blk < 0 || blk >= p.NB) {
+      if (have && lane == 0) atomicOr(p.err, 1u);
+      kr[0] = kr[1] = vr[0] = vr[1] = u32x4{0u, 0u, 0u, 0u};
+    } else {
+      const u32x4* ks = reinterpret_cast<const u32x4*>(kplane + (size_t)blk * p.block_elems);
+      const u32x4* vs = reinterpret_cast<const u32x4*>(kplane + (size_t)blk * p.block_elems + p.v_off);
+      kr[0] = ks[r0 * 64 + lane];
+      kr[1] = ks[(r0 + 1) * 64 + lane];
+      vr[0] = vs[r0 * 64 + lane];
+      vr[1] = vs[(r0 + 1) * 64 + lane];
+    }
+  };
+
+  issue(0);
+  for (int grp = 0; grp < ngroups; ++grp) {
+    const int tok0 = grp * kGroupTokens;
+    // ---- stage this wave's rows for everyone ----
+#pragma unroll
+    for (int rr = 0; rr < 2; ++rr) {
+      *reinterpret_cast<u32x4*>(k_lds + (sb * 16 + 4 * (r0 + rr) + kg) * RS + c16 * 16) = kr[rr];
+      if (tok0 + sb * 16 + 4 * (r0 + rr) + kg >= ntok) vr[rr] = u32x4{0u, 0u, 0u, 0u};   // may hold NaN
+    }
+#pragma unroll
+    for (int dt = 0; dt < EPL; ++dt) {
+      const uint32_t sel = (dt & 1) ? 0x07060302u : 0x05040100u;
+      va_lds[(dt * 64 + lane) * 4 + wave] = __builtin_amdgcn_perm(vr[1][dt >> 1], vr[0][dt >> 1], sel);
+    }
+    if (grp + 1 < ngroups) issue(grp + 1);
+    __syncthreads();
+
+    // ---- operands shared by this wave's column tiles ----
+    bf16x8 ka[2][KS], va[EPL];
+    const int trow_lds = 4 * (c16 & 3) + (c16 >> 2);
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        ka[b][ks] = __builtin_bit_cast(
+            bf16x8, *reinterpret_cast<const u32x4*>(k_lds + (b * 16 + trow_lds) * RS + (ks * 4 + kg) * 16));
+#pragma unroll
+    for (int dt = 0; dt < EPL; ++dt)
+      va[dt] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(&va_lds[(dt * 64 + lane) * 4]));
+    __syncthreads();   // everyone has its operands; the tiles may be overwritten
+
+#pragma unroll
+    for (int j = 0; j < kNQ; ++j) {
+      f32x4 sc[2];
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+        sc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+          sc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[b][ks], qb[j][ks], sc[b], 0, 0, 0);
+      }
+      // column = (position cpos[j], head cg[j]); token tok0 + 16b + 4r + kg at position tok_base + that
+      const int limit = pos0 + cpos[j] - tok_base;   // last visible token index within the item
+      float x[8];
+      float mx = NEG_INF;
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int t = tok0 + b * 16 + 4 * r + kg;
+          const bool ok = t < ntok && t <= limit;
+          const float v = ok ? sc[b][r] * p.scale_log2 : NEG_INF;
+          x[b * 4 + r] = v;
+          mx = fmaxf(mx, v);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m_run[j], mx);
+      const float m_ref = m_new == NEG_INF ? 0.f : m_new;   // a column that has seen no token yet
+      const float alpha = __builtin_exp2f(m_run[j] - m_ref);
+      bf16x8 pb;
+      float psum = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const __bf16 pj = (__bf16)__builtin_exp2f(x[i] - m_ref);
+        pb[i] = pj;
+        psum += (float)pj;
+      }
+      l_run[j] = l_run[j] * alpha + psum;
+      m_run[j] = m_new;
+#pragma unroll
+      for (int dt = 0; dt < EPL; ++dt) {
+        acc[j][dt] *= alpha;
+        acc[j][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pb, acc[j][dt], 0, 0, 0);
+      }
+    }
+  }
+
+  // ---- results: column-owned, no merge across waves ----
+  const int nch = (p.tile_base[tile + 1] - p.tile_base[tile]) / p.Hkv;
+  const size_t item = (size_t)p.item_first + blockIdx.x;
+#pragma unroll
+  for (int j = 0; j < kNQ; ++j) {
+    float l = l_run[j];
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+    const int col = (wave * kNQ + j) * 16 + c16;
+    if (nch == 1) {
+      if (cvalid[j]) {
+        float* orow = p.out + ((size_t)(row0 + cpos[j]) * p.Hq + (size_t)it.kv_head * G + cg[j]) * D;
+        const float inv = 1.0f / l;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          float* dst = orow + (kg * 4 + r) * EPL;
+#pragma unroll
+          for (int dt = 0; dt < EPL; dt += 4)
+            *reinterpret_cast<f32x4*>(dst + dt) = f32x4{acc[j][dt][r] * inv, acc[j][dt + 1][r] * inv,
+                                                        acc[j][dt + 2][r] * inv, acc[j][dt + 3][r] * inv};
+        }
+      }
+    } else {
+      float* prow = p.part_acc + (item * kTileColumns + col) * D;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        float* dst = prow + (kg * 4 + r) * EPL;
+#pragma unroll
+        for (int dt = 0; dt < EPL; dt += 4)
+          *reinterpret_cast<f32x4*>(dst + dt) = f32x4{acc[j][dt][r], acc[j][dt + 1][r], acc[j][dt + 2][r], acc[j][dt + 3][r]};
+      }
+      if (kg == 0) {
+        p.part_ml[(item * kTileColumns + col) * 2 + 0] = m_run[j];
+        p.part_ml[(item * kTileColumns + col) * 2 + 1] = l;
+      }
+    }
+  }
+}
+
+// Merge of the chunks of every (tile, kv head) that was split: log-sum-exp merge in chunk order.
+template <int D>
+__global__ __launch_bounds__(256) void prefill_merge_kernel(const PrefillParams p) {
+  const int tile = blockIdx.x / p.Hkv, head = blockIdx.x - tile * p.Hkv;
+  const int base = p.tile_base[tile];
+  const int nch = (p.tile_base[tile + 1] - base) / p.Hkv;
+  if (nch == 1) return;
+  const int row0 = p.tiles[4 * tile + 1], n_pos = p.tiles[4 * tile + 3];
+  const int G = p.G, gp_mask = (1 << p.gp_shift) - 1;
+  for (int e = threadIdx.x; e < kTileColumns * D; e += 256) {
+    const int col = e / D, d = e - col * D;
+    const int cpos = col >> p.gp_shift, cg = col & gp_mask;
+    if (cg >= G || cpos >= n_pos) continue;
+    float M = -INFINITY;
+    for (int c = 0; c < nch; ++c)
+      M = fmaxf(M, p.part_ml[(((size_t)base + (size_t)c * p.Hkv + head) * kTileColumns + col) * 2]);
+    float num = 0.f, den = 0.f;
+    for (int c = 0; c < nch; ++c) {
+      const size_t ic = ((size_t)base + (size_t)c * p.Hkv + head) * kTileColumns + col;
+      const float wt = __builtin_exp2f(p.part_ml[ic * 2] - M);   // 0 for a chunk this column cannot see
+      num += wt * p.part_acc[ic * D + d];
+      den += wt * p.part_ml[ic * 2 + 1];
+    }
+    p.out[((size_t)(row0 + cpos) * p.Hq + (size_t)head * G + cg) * D + d] = num / den;
+  }
+}
+
+// ---- host ---------------------------------------------------------------------------
+
+static int pf_check_bound(vkv_pool* p, const void* workspace, const char* who) {
+  if (!p) { set_error("%s: null pool", who); return VKV_E_INVAL; }
+  if (p->broken) { set_error("%s: pool unusable after a HIP failure", who); return VKV_E_HIP; }
+  if (!p->pf.has_plan) { set_error("%s: no plan; call kv_prefill_plan first", who); return VKV_E_STATE; }
+  if (!workspace || workspace != p->pf.bound_ws || p->pf.bound_gen != p->pf.gen) {
+    set_error("%s: workspace is not bound to the current plan; call kv_prefill_bind", who);
+    return VKV_E_STATE;
+  }
+  return VKV_OK;
+}
+
+static int pf_check_args(vkv_pool* p, int32_t layer, const void* q, const int32_t* table, int32_t max_blk,
+                         void* workspace, void* out, const char* who) {
+  int st = pf_check_bound(p, workspace, who);
+  if (st != VKV_OK) return st;
+  if (!p->cfg.base) { set_error("%s: pool has no device memory", who); return VKV_E_INVAL; }
+  if (p->cfg.head_dim != 128) { set_error("%s: prefill supports head_dim 128 only", who); return VKV_E_INVAL; }
+  if (layer < 0 || layer >= p->cfg.num_layers) { set_error("%s: layer %d out of range", who, layer); return VKV_E_INVAL; }
+  if (!q || !table || !out || (uintptr_t)q % 16 || (uintptr_t)out % 16) {
+    set_error("%s: q, out (16-byte aligned) and block_table must be given", who);
+    return VKV_E_INVAL;
+  }
+  if (max_blk < p->pf.max_ctx_blocks) {
+    set_error("%s: block table has %d columns, the plan needs %d", who, max_blk, p->pf.max_ctx_blocks);
+    return VKV_E_INVAL;
+  }
+  return VKV_OK;
+}
+
+static PrefillParams pf_params(vkv_pool* p, int32_t layer, const void* q, const int32_t* table, int32_t max_blk,
+                               void* workspace, void* out, float scale) {
+  const int D = p->cfg.head_dim;
+  char* ws = (char*)workspace;
+  PrefillParams a{};
+  a.pool = (const uint16_t*)p->cfg.base + (uint64_t)layer * ((uint64_t)2 * p->cfg.num_kv_heads * 16 * D);
+  a.work = (const WorkItem*)(ws + p->pf.off_work);
+  a.tiles = (const int32_t*)(ws + p->pf.off_tiles);
+  a.tile_base = (const int32_t*)(ws + p->pf.off_tile_base);
+  a.q = (const uint16_t*)q;
+  a.table = table;
+  a.part_acc = (float*)(ws + p->pf.off_acc);
+  a.part_ml = (float*)(ws + p->pf.off_ml);
+  a.out = (float*)out;
+  a.err = (uint32_t*)ws;
+  a.block_elems = p->block_elems;
+  a.v_off = (uint32_t)(p->cfg.num_kv_heads * 16 * D);
+  a.max_blk = max_blk;
+  a.Hq = p->cfg.num_q_heads;
+  a.Hkv = p->cfg.num_kv_heads;
+  a.G = p->G;
+  a.gp_shift = p->pf.gp_shift;
+  a.NB = p->cfg.num_blocks;
+  a.scale_log2 = (scale != 0.f ? scale : 1.0f / std::sqrt((float)D)) * 1.4426950408889634f;
+  return a;
+}
+
+static int pf_launch_slice(vkv_pool* p, int32_t layer, int32_t slice, const void* q, const int32_t* table,
+                           int32_t max_blk, void* workspace, void* out, float scale, hipStream_t st) {
+  PrefillParams a = pf_params(p, layer, q, table, max_blk, workspace, out, scale);
+  a.item_first = p->pf.slice_start[slice];
+  const int32_t count = p->pf.slice_start[slice + 1] - a.item_first;
+  ProfScope prof(p, VKV_PROF_PREFILL, slice, st);
+  hipLaunchKernelGGL(paged_prefill_attn_slice_kernel<128>, dim3((unsigned)count), dim3(256), 0, st, a);
+  VKV_HIP(hipGetLastError());
+  return VKV_OK;
+}
+
+static int pf_launch_merge(vkv_pool* p, void* workspace, void* out, hipStream_t st) {
+  PrefillParams a = pf_params(p, 0, workspace, nullptr, 0, workspace, out, 0.f);
+  const int32_t n_tiles = (int32_t)p->pf.tile_base.size() - 1;
+  ProfScope prof(p, VKV_PROF_PREFILL_MERGE, 0, st);
+  hipLaunchKernelGGL(prefill_merge_kernel<128>, dim3((unsigned)(n_tiles * p->cfg.num_kv_heads)), dim3(256), 0, st, a);
+  VKV_HIP(hipGetLastError());
+  return VKV_OK;
+}
+
+}  // namespace vkv
+
+using namespace vkv;
+
+extern "C" {
+
+int kv_prefill_plan(vkv_pool* p, const int32_t* ctx, const int32_t* q_len, int32_t S, uint64_t slice_bytes,
+                    int32_t chunk_tokens, vkv_prefill_plan_info* info) {
+  if (!p || !ctx || !q_len || S < 1) { set_error("kv_prefill_plan: bad argument"); return VKV_E_INVAL; }
+  if (chunk_tokens < kGroupTokens || chunk_tokens % kGroupTokens || chunk_tokens > kMaxChunkTokens) {
+    set_error("kv_prefill_plan: chunk_tokens must be a multiple of %d in [%d, %d]", kGroupTokens, kGroupTokens,
+              kMaxChunkTokens);
+    return VKV_E_INVAL;
+  }
+  const int Hkv = p->cfg.num_kv_heads, D = p->cfg.head_dim, B = p->cfg.block_tokens, G = p->G;
+  int gp_shift = 0;
+  while ((1 << gp_shift) < G) ++gp_shift;
+  const int QP = kTileColumns >> gp_shift;   // positions per tile
+  vkv_pool::PrefillPlan pl;
+  pl.gp_shift = gp_shift;
+  pl.tile_positions = QP;
+  pl.num_seqs = S;
+  int64_t row = 0;
+  double flops = 0.0;
+  uint64_t total = 0, max_slice = 0;
+  for (int32_t s = 0; s < S; ++s) {
+    if (q_len[s] < 1 || ctx[s] < q_len[s]) {
+      set_error("kv_prefill_plan: sequence %d needs 1 <= q_len (%d) <= context length (%d)", s, q_len[s], ctx[s]);
+      return VKV_E_INVAL;
+    }
+    pl.max_ctx_blocks = std::max(pl.max_ctx_blocks, (ctx[s] + B - 1) / B);
+    const int32_t q0 = ctx[s] - q_len[s];
+    for (int32_t t = 0; t * QP < q_len[s]; ++t) {
+      const int32_t n_pos = std::min(QP, q_len[s] - t * QP), pos0 = q0 + t * QP, visible = pos0 + n_pos;
+      const int32_t tile = (int32_t)pl.tile_base.size();
+      pl.tiles.insert(pl.tiles.end(), {s, (int32_t)(row + (int64_t)t * QP), pos0, n_pos});
+      pl.tile_base.push_back((int32_t)pl.work.size());
+      for (int32_t first = 0; first < visible; first += chunk_tokens) {
+        const int32_t nt = std::min(chunk_tokens, visible - first);
+        for (int32_t h = 0; h < Hkv; ++h) pl.work.push_back(WorkItem{tile, h, first / B, nt});
+      }
+      if (pl.work.size() > 0x7FFFFF00u) { set_error("kv_prefill_plan: too many work items"); return VKV_E_INVAL; }
+      for (int32_t i = 0; i < n_pos; ++i) flops += 4.0 * D * p->cfg.num_q_heads * (double)(pos0 + i + 1);
+    }
+    row += q_len[s];
+  }
+  if (row > 0x7FFFFFF0ll) { set_error("kv_prefill_plan: too many query rows"); return VKV_E_INVAL; }
+  pl.total_q = (int32_t)row;
+  pl.tile_base.push_back((int32_t)pl.work.size());
+  const uint64_t token_bytes = (uint64_t)2 * D * 2;
+  pl.slice_start.push_back(0);
+  uint64_t acc = 0;
+  for (size_t i = 0; i < pl.work.size(); ++i) {
+    const uint64_t b = (uint64_t)pl.work[i].n_tokens * token_bytes;
+    if ((int32_t)i > pl.slice_start.back() && acc + b > slice_bytes) {
+      max_slice = std::max(max_slice, acc);
+      pl.slice_start.push_back((int32_t)i);
+      acc = 0;
+    }
+    acc += b;
+    total += b;
+  }
+  max_slice = std::max(max_slice, acc);
+  pl.slice_start.push_back((int32_t)pl.work.size());
+  const uint64_t n_items = pl.work.size(), n_tiles = pl.tile_base.size() - 1;
+  pl.off_work = 256;
+  pl.off_tiles = pl.off_work + n_items * sizeof(WorkItem);
+  pl.off_tile_base = pl.off_tiles + n_tiles * 16;
+  pl.upload_bytes = pl.off_tile_base + (n_tiles + 1) * 4;
+  pl.off_ml = align_up(pl.upload_bytes, 256);
+  pl.off_acc = align_up(pl.off_ml + n_items * kTileColumns * 2 * 4, 256);
+  pl.total = align_up(pl.off_acc + n_items * kTileColumns * (uint64_t)D * 4, 256);
+  pl.has_plan = true;
+  pl.gen = p->pf.gen + 1;
+  p->pf = std::move(pl);
+  if (info) {
+    info->n_items = (int32_t)n_items;
+    info->n_slices = (int32_t)p->pf.slice_start.size() - 1;
+    info->n_tiles = (int32_t)n_tiles;
+    info->tile_positions = QP;
+    info->total_q = p->pf.total_q;
+    info->reserved = 0;
+    info->workspace_bytes = p->pf.total;
+    info->kv_bytes_per_layer = total;
+    info->max_slice_kv_bytes = max_slice;
+    info->flops_per_layer = flops;
+  }
+  return VKV_OK;
+}
+
+int kv_prefill_plan_read(vkv_pool* p, int32_t* work_out, int32_t* slice_start_out, int32_t* tiles_out,
+                         int32_t* tile_base_out) {
+  if (!p) { set_error("kv_prefill_plan_read: null pool"); return VKV_E_INVAL; }
+  if (!p->pf.has_plan) { set_error("kv_prefill_plan_read: no plan"); return VKV_E_STATE; }
+  if (work_out) std::memcpy(work_out, p->pf.work.data(), p->pf.work.size() * sizeof(WorkItem));
+  if (slice_start_out) std::memcpy(slice_start_out, p->pf.slice_start.data(), p->pf.slice_start.size() * 4);
+  if (tiles_out) std::memcpy(tiles_out, p->pf.tiles.data(), p->pf.tiles.size() * 4);
+  if (tile_base_out) std::memcpy(tile_base_out, p->pf.tile_base.data(), p->pf.tile_base.size() * 4);
+  return VKV_OK;
+}
+
+int kv_prefill_bind(vkv_pool* p, void* workspace, uint64_t workspace_bytes, void* stream) {
+  if (!p) { set_error("kv_prefill_bind: null pool"); return VKV_E_INVAL; }
+  if (p->broken) { set_error("kv_prefill_bind: pool unusable after a HIP failure"); return VKV_E_HIP; }
+  if (!p->pf.has_plan) { set_error("kv_prefill_bind: no plan"); return VKV_E_STATE; }
+  if (!workspace || (uintptr_t)workspace % 256 || workspace_bytes < p->pf.total) {
+    set_error("kv_prefill_bind: workspace must be 256-byte aligned and hold %llu bytes", (unsigned long long)p->pf.total);
+    return VKV_E_INVAL;
+  }
+  int st = ensure_stage(p, p->pf.upload_bytes);
+  if (st != VKV_OK) return st;
+  char* h = (char*)p->stage;
+  std::memset(h, 0, 256);
+  std::memcpy(h + p->pf.off_work, p->pf.work.data(), p->pf.work.size() * sizeof(WorkItem));
+  std::memcpy(h + p->pf.off_tiles, p->pf.tiles.data(), p->pf.tiles.size() * 4);
+  std::memcpy(h + p->pf.off_tile_base, p->pf.tile_base.data(), p->pf.tile_base.size() * 4);
+  VKV_HIP(hipMemcpyAsync(workspace, h, p->pf.upload_bytes, hipMemcpyHostToDevice, (hipStream_t)stream));
+  VKV_HIP(hipEventRecord(p->stage_ev, (hipStream_t)stream));
+  p->stage_inflight = true;
+  p->pf.bound_ws = workspace;
+  p->pf.bound_gen = p->pf.gen;
+  return VKV_OK;
+}
+
+int paged_prefill_attn_slice(vkv_pool* p, int32_t layer, int32_t slice, const void* q, const int32_t* table,
+                             int32_t max_blk, void* workspace, void* out, float scale, void* stream) {
+  int st = pf_check_args(p, layer, q, table, max_blk, workspace, out, "paged_prefill_attn_slice");
+  if (st != VKV_OK) return st;
+  if (slice < 0 || slice >= (int32_t)p->pf.slice_start.size() - 1) {
+    set_error("paged_prefill_attn_slice: slice %d out of range [0,%d)", slice, (int)p->pf.slice_start.size() - 1);
+    return VKV_E_INVAL;
+  }
+  return pf_launch_slice(p, layer, slice, q, table, max_blk, workspace, out, scale, (hipStream_t)stream);
+}
+
+int kv_prefill_merge(vkv_pool* p, void* workspace, void* out, void* stream) {
+  int st = pf_check_bound(p, workspace, "kv_prefill_merge");
+  if (st != VKV_OK) return st;
+  if (!out) { set_error("kv_prefill_merge: null output"); return VKV_E_INVAL; }
+  return pf_launch_merge(p, workspace, out, (hipStream_t)stream);
+}
+
+int kv_prefill_run_layer(vkv_pool* p, int32_t layer, int32_t* cursor, const void* q, const int32_t* table,
+                         int32_t max_blk, void* workspace, void* out, float scale, int32_t max_inflight,
+                         void* stream) {
+  int st = pf_check_args(p, layer, q, table, max_blk, workspace, out, "kv_prefill_run_layer");
+  if (st != VKV_OK) return st;
+  hipStream_t hs = (hipStream_t)stream;
+  return run_slices(p, cursor, (int32_t)p->pf.slice_start.size() - 1, max_inflight, hs, "kv_prefill_run_layer",
+                    [&](int32_t s) { return pf_launch_slice(p, layer, s, q, table, max_blk, workspace, out, scale, hs); },
+                    [&]() { return pf_launch_merge(p, workspace, out, hs); });
+}
+
+int kv_prefill_check(vkv_pool* p, void* workspace, void* stream) {
+  int st = pf_check_bound(p, workspace, "kv_prefill_check");
+  if (st != VKV_OK) return st;
+  VKV_HIP(hipStreamSynchronize((hipStream_t)stream));
+  uint32_t flag = 0;
+  VKV_HIP(hipMemcpy(&flag, workspace, 4, hipMemcpyDeviceToHost));
+  if (flag) { set_error("kv_prefill_check: a slice met a block-table entry outside the pool"); return VKV_E_STATE; }
+  return VKV_OK;
+}
+
+}  // extern "C"

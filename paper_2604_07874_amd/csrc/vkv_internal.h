@@ -7,6 +7,7 @@
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
+#include <functional>
 #include <mutex>
 #include <string>
 #include <utility>
@@ -89,6 +90,19 @@ struct vkv_pool {
   void* bound_ws = nullptr;
   uint64_t bound_gen = 0;
 
+  // prefill plan (host) and its binding; see prefill.hip
+  struct PrefillPlan {
+    bool has_plan = false;
+    uint64_t gen = 0, bound_gen = 0;
+    void* bound_ws = nullptr;
+    int32_t num_seqs = 0, total_q = 0, max_ctx_blocks = 0, gp_shift = 0, tile_positions = 0;
+    std::vector<vkv::WorkItem> work;       // .seq holds the tile id
+    std::vector<int32_t> slice_start;
+    std::vector<int32_t> tiles;            // [n_tiles][4] = (sequence, first q row, first position, positions)
+    std::vector<int32_t> tile_base;        // first item of each tile (+1 sentinel)
+    uint64_t off_work = 0, off_tiles = 0, off_tile_base = 0, off_ml = 0, off_acc = 0, upload_bytes = 0, total = 0;
+  } pf;
+
   // pinned staging (allocated on first device use)
   void* stage = nullptr;
   size_t stage_cap = 0;
@@ -141,6 +155,10 @@ struct ProfScope {
     if (slot >= 0) (void)hipEventRecord(p->prof_ev[2 * slot + 1], st);
   }
 };
+
+// Slice scheduler shared by decode and prefill (attn.hip).
+int run_slices(vkv_pool* p, int32_t* cursor, int32_t n_slices, int32_t max_inflight, hipStream_t hs, const char* who,
+               const std::function<int(int32_t)>& launch, const std::function<int()>& tail);
 
 // Host-side relocation plan; see kv_reclaim_plan.
 int plan_relocation(const vkv_pool* p, int32_t lo, int32_t hi,

@@ -36,3 +36,35 @@ def test_plan_rejects_bad_arguments():
         attention_plan([5], 1, 64, 16, 24, 100)
     with pytest.raises(ValueError):
         attention_plan([5, 0], 1, 64, 16, 32, 100)
+
+
+def test_prefill_plan_covers_every_query_token_pair_once():
+    from oracle.plan import prefill_plan
+    ctx, qlen, Hq, Hkv = [300, 77, 2100, 40], [300, 5, 130, 40], 8, 2      # G = 4 -> 32 positions per tile
+    work, starts, tiles, tile_base = prefill_plan(ctx, qlen, Hq, Hkv, 128, 16, 256, 300000)
+    assert tile_base[0] == 0 and tile_base[-1] == len(work) and len(tile_base) == len(tiles) + 1
+    rows = 0
+    seen = set()
+    for k, (s, row0, pos0, n_pos) in enumerate(tiles.tolist()):
+        assert 1 <= n_pos <= 32 and pos0 + n_pos <= ctx[s] and pos0 >= ctx[s] - qlen[s]
+        items = work[tile_base[k]:tile_base[k + 1]]
+        assert len(items) % Hkv == 0 and np.all(items[:, 0] == k)
+        for h in range(Hkv):
+            mine = items[items[:, 1] == h]
+            covered = []
+            for _, _, fb, nt in mine.tolist():
+                assert 1 <= nt <= 256 and (fb * 16) % 256 == 0
+                covered.extend(range(fb * 16, fb * 16 + nt))
+            assert covered == list(range(pos0 + n_pos))          # exactly what the tile's last position sees
+        for i in range(n_pos):
+            assert (s, pos0 + i) not in seen
+            seen.add((s, pos0 + i))
+        rows += n_pos
+    assert rows == sum(qlen) and seen == {(s, ctx[s] - qlen[s] + i) for s in range(4) for i in range(qlen[s])}
+    # q rows are packed sequence after sequence, tile after tile
+    assert tiles[:, 1].tolist() == np.concatenate([[0], np.cumsum(tiles[:, 3])[:-1]]).tolist()
+    nbytes = work[:, 3].astype(np.int64) * 512
+    for a, b in zip(starts[:-1], starts[1:]):
+        assert int(nbytes[a:b].sum()) <= 300000 or b - a == 1
+        if b < len(work):
+            assert int(nbytes[a:b].sum()) + int(nbytes[b]) > 300000

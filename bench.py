@@ -63,6 +63,10 @@ def main():
     ap.add_argument("--concurrent-reclaim", action="store_true",
                     help="extra leg: rate-capped, chunked reclamation on a second stream while decode runs")
     ap.add_argument("--rate-cap", type=float, default=None, help="bytes/s for the concurrent leg")
+    ap.add_argument("--prefill-leg", action="store_true",
+                    help="extra leg: causal prefill of the newest --prefill-tokens tokens of every sequence")
+    ap.add_argument("--prefill-tokens", type=int, default=2048)
+    ap.add_argument("--prefill-slice-bytes", type=int, default=512 << 20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-launch-events", action="store_true",
                     help="do not bracket launches with timing events (roofline fields become null)")
@@ -306,6 +310,44 @@ def main():
             "concurrent_reclaim_launches": int(crs.n_chunks),
             "concurrent_decode_GBps": round((n_b - n_a) * decode_bytes_layer / (t_b - t_a) / 1e9, 1),
         })
+
+    # ---- optional: preemptible causal prefill over the same pool (MFMA-bound) -------------
+    if args.prefill_leg:
+        q_len = np.minimum(st.ctx_len, args.prefill_tokens).astype(np.int32)
+        pinfo = vkv.kv_prefill_plan(pool, st.ctx_len, q_len, args.prefill_slice_bytes, 2048)
+        pws = torch.empty(pinfo.workspace_bytes, dtype=torch.uint8, device=dev)
+        vkv.kv_prefill_bind(pool, pws, stream)
+        pq = torch.empty((pinfo.total_q, g.num_q_heads, g.head_dim), dtype=torch.int16, device=dev)
+        # query values: the generator's bits at the start of the pool serve as well as any
+        pq.view(-1).copy_(pool_t[:pq.numel()])
+        pout = torch.empty((pinfo.total_q, g.num_q_heads, g.head_dim), dtype=torch.float32, device=dev)
+        vkv.kv_profile_enable(pool, pinfo.n_slices * 3 + 16)
+        n_layers_p = min(L, 2)
+        for layer in range(n_layers_p):           # warm-up
+            vkv.kv_prefill_run_layer(pool, layer, 0, pq, tables, pws, pout, max_inflight=args.max_inflight, stream=stream)
+        torch.cuda.synchronize()
+        vkv.kv_profile_read(pool, 1 << 20)
+        t0 = time.perf_counter()
+        for layer in range(n_layers_p):
+            vkv.kv_prefill_run_layer(pool, layer, 0, pq, tables, pws, pout, max_inflight=args.max_inflight, stream=stream)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / n_layers_p
+        rec = vkv.kv_profile_read(pool, 1 << 20)
+        psl = rec[rec["kind"] == vkv.VKV_PROF_PREFILL]
+        vkv.kv_profile_enable(pool, 0)
+        kern_s = float(psl["ms"].sum()) * 1e-3 / n_layers_p
+        extra.update({
+            "prefill_rows": int(pinfo.total_q), "prefill_slices_per_layer": int(pinfo.n_slices),
+            "prefill_items_per_layer": int(pinfo.n_items),
+            "prefill_TFLOPs_wall": round(pinfo.flops_per_layer / dt / 1e12, 1),
+            "prefill_TFLOPs_kernel": round(pinfo.flops_per_layer / kern_s / 1e12, 1),
+            "prefill_frac_of_mfma_bf16_peak": round(pinfo.flops_per_layer / kern_s / 2.5e15, 4),
+            "prefill_ms_per_layer": round(dt * 1e3, 3),
+            "prefill_slice_us_p50": round(percentile(psl["ms"], 50) * 1e3, 1),
+            "prefill_slice_us_p99": round(percentile(psl["ms"], 99) * 1e3, 1),
+            "prefill_kv_GBps": round(pinfo.kv_bytes_per_layer / kern_s / 1e9, 1),
+        })
+        del pws, pq, pout
 
     # ---- the CPU oracle on a bounded sample of the same workload --------------------
     cpu_baseline = None

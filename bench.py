@@ -66,7 +66,8 @@ def main():
     ap.add_argument("--prefill-leg", action="store_true",
                     help="extra leg: causal prefill of the newest --prefill-tokens tokens of every sequence")
     ap.add_argument("--prefill-tokens", type=int, default=2048)
-    ap.add_argument("--prefill-slice-bytes", type=int, default=512 << 20)
+    ap.add_argument("--prefill-slice-bytes", type=int, default=1 << 30)
+    ap.add_argument("--prefill-chunk-tokens", type=int, default=4096)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-launch-events", action="store_true",
                     help="do not bracket launches with timing events (roofline fields become null)")
@@ -314,7 +315,7 @@ def main():
     # ---- optional: preemptible causal prefill over the same pool (MFMA-bound) -------------
     if args.prefill_leg:
         q_len = np.minimum(st.ctx_len, args.prefill_tokens).astype(np.int32)
-        pinfo = vkv.kv_prefill_plan(pool, st.ctx_len, q_len, args.prefill_slice_bytes, 2048)
+        pinfo = vkv.kv_prefill_plan(pool, st.ctx_len, q_len, args.prefill_slice_bytes, args.prefill_chunk_tokens)
         pws = torch.empty(pinfo.workspace_bytes, dtype=torch.uint8, device=dev)
         vkv.kv_prefill_bind(pool, pws, stream)
         pq = torch.empty((pinfo.total_q, g.num_q_heads, g.head_dim), dtype=torch.int16, device=dev)

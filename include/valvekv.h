@@ -266,7 +266,7 @@ typedef struct vkv_prefill_plan_info {
  * paper finds coarse preemption costliest (Section 2.2, Section 5).
  *   - the new tokens of a sequence are cut into tiles of tile_positions positions;
  *   - the tokens a tile can see (0 .. its last position) are cut into chunks of
- *     chunk_tokens (multiple of 32 in [32, 2048]);
+ *     chunk_tokens (multiple of 32 in [32, 16384]);
  *   - work item = (tile, kv head, chunk), order tile, chunk, kv head;
  *   - a slice is a maximal run of items reading at most slice_bytes of K+V.
  * Query rows are packed: sequence s owns rows sum(q_len[:s]) .. + q_len[s].

@@ -2,7 +2,10 @@
 // through the C ABI, with no Python in the process (rocprofv3 --pmc -- ./vkv_pmc_driver).
 // It is also the smallest complete example of the call sequence a framework would use.
 //
-//   vkv_pmc_driver [layers=32] [steps=2] [pool_GiB=40]
+//   vkv_pmc_driver [layers=32] [steps=2] [pool_GiB=40] [prefill_tokens=0] [prefill_slice_MiB=1024] [prefill_chunk=4096]
+//
+// With prefill_tokens > 0 one layer of causal prefill of the newest min(context, prefill_tokens)
+// tokens of every sequence runs after the decode/reclaim steps.
 //
 // Inputs are synthetic: contexts ~ lognormal(median 2048, sigma 0.7) clipped to [16, 8192],
 // 64 sequences, 32 query / 8 KV heads of 128, 70 % of the pool's 2 MiB blocks live at random
@@ -53,6 +56,9 @@ int main(int argc, char** argv) {
   const int L = argc > 1 ? std::atoi(argv[1]) : 32;
   const int steps = argc > 2 ? std::atoi(argv[2]) : 2;
   const int pool_gib = argc > 3 ? std::atoi(argv[3]) : 40;
+  const int prefill_tokens = argc > 4 ? std::atoi(argv[4]) : 0;
+  const uint64_t prefill_slice = (uint64_t)(argc > 5 ? std::atoi(argv[5]) : 1024) << 20;
+  const int prefill_chunk = argc > 6 ? std::atoi(argv[6]) : 4096;
   const int S = 64, Hq = 32, Hkv = 8, D = 128, B = 16;
   const size_t block_elems = (size_t)L * 2 * Hkv * B * D;
   const size_t block_bytes = block_elems * 2;
@@ -133,6 +139,25 @@ int main(int argc, char** argv) {
   }
   VK(kv_attn_check(pool, ws, nullptr));
   CK(hipDeviceSynchronize());
+  if (prefill_tokens > 0) {
+    std::vector<int32_t> q_len(S);
+    for (int s = 0; s < S; ++s) q_len[s] = std::min(ctx[s], prefill_tokens);
+    vkv_prefill_plan_info pinfo{};
+    VK(kv_prefill_plan(pool, ctx.data(), q_len.data(), S, prefill_slice, prefill_chunk, &pinfo));
+    void* pws;
+    uint16_t* pq;
+    float* pout;
+    CK(hipMalloc(&pws, pinfo.workspace_bytes));
+    CK(hipMalloc(&pq, (size_t)pinfo.total_q * Hq * D * 2));
+    CK(hipMalloc(&pout, (size_t)pinfo.total_q * Hq * D * 4));
+    hipLaunchKernelGGL(fill_bf16, dim3(1024), dim3(256), 0, 0, pq, (size_t)pinfo.total_q * Hq * D, 3u);
+    VK(kv_prefill_bind(pool, pws, pinfo.workspace_bytes, nullptr));
+    int32_t cursor = 0;
+    VK(kv_prefill_run_layer(pool, 0, &cursor, pq, tables_d, max_blk, pws, pout, 0.f, 2, nullptr));
+    VK(kv_prefill_check(pool, pws, nullptr));
+    std::printf("prefill: %d rows, %d items, %d slices, %.3e flops, %llu kv bytes\n", pinfo.total_q, pinfo.n_items,
+                pinfo.n_slices, pinfo.flops_per_layer, (unsigned long long)pinfo.kv_bytes_per_layer);
+  }
   VK(kv_pool_destroy(pool));
   std::printf("done\n");
   return 0;

@@ -35,12 +35,16 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kTileColumns = 128;   // (position, query head) columns of one query tile
 constexpr int kNQ = 2;              // 16-column MFMA tiles per wave
+constexpr int kMaxPrefillChunkTokens = 16384;   // bounds an item's run time, not a kernel limit
+constexpr float kSlack = 8.0f;      // how far (log2 units) a score may exceed the running reference
+constexpr float kNoMax = -1.0e30f;  // reference of a column that has seen no token yet (finite on purpose)
 
 struct PrefillParams {
   const uint16_t* pool;       // pool base + layer offset (elements)
   const WorkItem* work;       // .seq = tile id
   const int32_t* tiles;       // [n_tiles][4] = (sequence, first q row, first position, positions)
   const int32_t* tile_base;   // [n_tiles + 1]
+  const int32_t* order;       // [n_items] launch order: within a slice, items by falling token count
   const uint16_t* q;          // [total_q][Hq][D]
   const int32_t* table;
   float* part_acc;            // [n_items][128][D]
@@ -61,14 +65,16 @@ __global__ __launch_bounds__(256, 2) void paged_prefill_attn_slice_kernel(const 
   constexpr int RS = D * 2 + 16;
   constexpr float NEG_INF = -INFINITY;
 
-  __shared__ __attribute__((aligned(16))) unsigned char k_lds[32 * RS];
-  __shared__ __attribute__((aligned(16))) uint32_t va_lds[EPL * 64 * 4];
+  // two staging buffers: a group is staged while the previous one may still be read
+  __shared__ __attribute__((aligned(16))) unsigned char k_lds2[2][32 * RS];
+  __shared__ __attribute__((aligned(16))) uint32_t va_lds2[2][EPL * 64 * 4];
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int c16 = lane & 15, kg = lane >> 4;
 
-  const WorkItem it = p.work[p.item_first + blockIdx.x];
+  const int item_id = p.order[p.item_first + blockIdx.x];   // longest items of the slice start first
+  const WorkItem it = p.work[item_id];
   const int tile = it.seq;
   const int seq = p.tiles[4 * tile + 0], row0 = p.tiles[4 * tile + 1], pos0 = p.tiles[4 * tile + 2],
             n_pos = p.tiles[4 * tile + 3];
@@ -100,54 +106,77 @@ __global__ __launch_bounds__(256, 2) void paged_prefill_attn_slice_kernel(const 
   const int32_t* trow = p.table + (size_t)seq * p.max_blk + it.first_block;
   const uint16_t* kplane = p.pool + (size_t)it.kv_head * (16 * D);
   const int nblk_item = (ntok + 15) >> 4;
-  const int32_t tb0 = lane < nblk_item ? trow[lane] : -1;
-  const int32_t tb1 = 64 + lane < nblk_item ? trow[64 + lane] : -1;
+  // block ids of the item, 64 at a time: lane i of tb0 holds entry 64 win + i, tb1 the 64 after those
+  int32_t tb0 = lane < nblk_item ? trow[lane] : -1;
+  int32_t tb1 = 64 + lane < nblk_item ? trow[64 + lane] : -1;
+  int win = 0;
 
-  f32x4 acc[kNQ][EPL];
-  float m_run[kNQ], l_run[kNQ];
+  f32x4 acc[kNQ][EPL], accl[kNQ];
+  float m_run[kNQ];
 #pragma unroll
   for (int j = 0; j < kNQ; ++j) {
-    m_run[j] = NEG_INF;
-    l_run[j] = 0.f;
+    m_run[j] = kNoMax;
+    accl[j] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int dt = 0; dt < EPL; ++dt) acc[j][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
+  bf16x8 ones;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) ones[i] = (__bf16)1.0f;
+  // last token index (within the item) that every column of this wave may see
+  const int wave_limit = pos0 + ((wave * kNQ * 16) >> p.gp_shift) - tok_base;
+
   // this wave's share of a group: rows 4r+kg, r in {r0, r0+1}, of block (wave >> 1)
   const int sb = wave >> 1, r0 = (wave & 1) * 2;
-  u32x4 kr[2], vr[2];
-  auto issue = [&](int grp) {
+  struct Rows { u32x4 k[2], v[2]; };
+  auto fetch = [&](int grp) -> Rows {
+    Rows x;
     const int bi = grp * 2 + sb;
     const bool have = bi < nblk_item;
-    const int32_t blk = bi < 64 ? __builtin_amdgcn_readlane(tb0, bi & 63) : __builtin_amdgcn_readlane(tb1, bi & 63);
+    if ((bi >> 6) != win) {   // groups are fetched in rising order, so the window moves one step at a time
+      win = bi >> 6;
+      tb0 = tb1;
+      tb1 = (win + 1) * 64 + lane < nblk_item ? trow[(win + 1) * 64 + lane] : -1;
+    }
+    const int32_t blk = __builtin_amdgcn_readlane(tb0, bi & 63);
     if (blk < 0 || blk >= p.NB) {
       if (have && lane == 0) atomicOr(p.err, 1u);
-      kr[0] = kr[1] = vr[0] = vr[1] = u32x4{0u, 0u, 0u, 0u};
+      x.k[0] = x.k[1] = x.v[0] = x.v[1] = u32x4{0u, 0u, 0u, 0u};
     } else {
       const u32x4* ks = reinterpret_cast<const u32x4*>(kplane + (size_t)blk * p.block_elems);
       const u32x4* vs = reinterpret_cast<const u32x4*>(kplane + (size_t)blk * p.block_elems + p.v_off);
-      kr[0] = ks[r0 * 64 + lane];
-      kr[1] = ks[(r0 + 1) * 64 + lane];
-      vr[0] = vs[r0 * 64 + lane];
-      vr[1] = vs[(r0 + 1) * 64 + lane];
+      x.k[0] = ks[r0 * 64 + lane];
+      x.k[1] = ks[(r0 + 1) * 64 + lane];
+      x.v[0] = vs[r0 * 64 + lane];
+      x.v[1] = vs[(r0 + 1) * 64 + lane];
     }
+    return x;
   };
 
-  issue(0);
+  // two groups of loads in flight per wave: the compute of one group is shorter than a memory round trip
+  Rows cur = fetch(0), nx1 = cur;
+  if (1 < ngroups) nx1 = fetch(1);
   for (int grp = 0; grp < ngroups; ++grp) {
     const int tok0 = grp * kGroupTokens;
+    unsigned char* k_lds = k_lds2[grp & 1];
+    uint32_t* va_lds = va_lds2[grp & 1];
     // ---- stage this wave's rows for everyone ----
 #pragma unroll
     for (int rr = 0; rr < 2; ++rr) {
-      *reinterpret_cast<u32x4*>(k_lds + (sb * 16 + 4 * (r0 + rr) + kg) * RS + c16 * 16) = kr[rr];
-      if (tok0 + sb * 16 + 4 * (r0 + rr) + kg >= ntok) vr[rr] = u32x4{0u, 0u, 0u, 0u};   // may hold NaN
+      *reinterpret_cast<u32x4*>(k_lds + (sb * 16 + 4 * (r0 + rr) + kg) * RS + c16 * 16) = cur.k[rr];
+      if (tok0 + kGroupTokens > ntok && tok0 + sb * 16 + 4 * (r0 + rr) + kg >= ntok)
+        cur.v[rr] = u32x4{0u, 0u, 0u, 0u};   // rows past the end may hold NaN
     }
 #pragma unroll
     for (int dt = 0; dt < EPL; ++dt) {
       const uint32_t sel = (dt & 1) ? 0x07060302u : 0x05040100u;
-      va_lds[(dt * 64 + lane) * 4 + wave] = __builtin_amdgcn_perm(vr[1][dt >> 1], vr[0][dt >> 1], sel);
+      va_lds[(dt * 64 + lane) * 4 + wave] = __builtin_amdgcn_perm(cur.v[1][dt >> 1], cur.v[0][dt >> 1], sel);
     }
-    if (grp + 1 < ngroups) issue(grp + 1);
+    cur = nx1;
+    if (grp + 2 < ngroups) nx1 = fetch(grp + 2);
+    // one barrier per group: the buffer written now was last read two groups ago, and every wave has
+    // passed the previous group's barrier since
     __syncthreads();
 
     // ---- operands shared by this wave's column tiles ----
@@ -162,8 +191,10 @@ __global__ __launch_bounds__(256, 2) void paged_prefill_attn_slice_kernel(const 
 #pragma unroll
     for (int dt = 0; dt < EPL; ++dt)
       va[dt] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(&va_lds[(dt * 64 + lane) * 4]));
-    __syncthreads();   // everyone has its operands; the tiles may be overwritten
 
+    // A group is interior for this wave when every token of it exists and is visible to every column of
+    // the wave; only the groups on the causal diagonal and a ragged last group need the mask.
+    const bool interior = tok0 + kGroupTokens <= ntok && tok0 + kGroupTokens - 1 <= wave_limit;
 #pragma unroll
     for (int j = 0; j < kNQ; ++j) {
       f32x4 sc[2];
@@ -174,51 +205,49 @@ __global__ __launch_bounds__(256, 2) void paged_prefill_attn_slice_kernel(const 
         for (int ks = 0; ks < KS; ++ks)
           sc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[b][ks], qb[j][ks], sc[b], 0, 0, 0);
       }
-      // column = (position cpos[j], head cg[j]); token tok0 + 16b + 4r + kg at position tok_base + that
-      const int limit = pos0 + cpos[j] - tok_base;   // last visible token index within the item
-      float x[8];
-      float mx = NEG_INF;
+      if (!interior) {
+        // column = (position cpos[j], head cg[j]); token tok0 + 16b + 4r + kg sits at position tok_base + that
+        const int limit = min(pos0 + cpos[j] - tok_base, ntok - 1);   // last visible token index within the item
 #pragma unroll
-      for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < 2; ++b)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int t = tok0 + b * 16 + 4 * r + kg;
-          const bool ok = t < ntok && t <= limit;
-          const float v = ok ? sc[b][r] * p.scale_log2 : NEG_INF;
-          x[b * 4 + r] = v;
-          mx = fmaxf(mx, v);
-        }
-      mx = fmaxf(mx, __shfl_xor(mx, 16));
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run[j], mx);
-      const float m_ref = m_new == NEG_INF ? 0.f : m_new;   // a column that has seen no token yet
-      const float alpha = __builtin_exp2f(m_run[j] - m_ref);
+          for (int r = 0; r < 4; ++r)
+            if (tok0 + b * 16 + 4 * r + kg > limit) sc[b][r] = NEG_INF;   // also drops NaN from rows past the end
+      }
+      // The running reference m_run follows the column maximum lazily: it moves only when some score
+      // exceeds it by more than kSlack (log2 units), so p stays below 2^kSlack and most groups skip
+      // both the cross-lane maximum and the rescaling of the accumulators.
+      const float mx = fmaxf(fmaxf(fmaxf(sc[0][0], sc[0][1]), fmaxf(sc[0][2], sc[0][3])),
+                             fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
+      if (__builtin_amdgcn_ballot_w64(fmaf(mx, p.scale_log2, -kSlack) > m_run[j]) != 0ull) {
+        float mc = fmaxf(mx, __shfl_xor(mx, 16));
+        mc = fmaxf(mc, __shfl_xor(mc, 32));
+        const float m_new = fmaxf(m_run[j], mc * p.scale_log2);
+        const float alpha = __builtin_amdgcn_exp2f(m_run[j] - m_new);
+        m_run[j] = m_new;
+        accl[j] *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < EPL; ++dt) acc[j][dt] *= alpha;
+      }
       bf16x8 pb;
-      float psum = 0.f;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const __bf16 pj = (__bf16)__builtin_exp2f(x[i] - m_ref);
-        pb[i] = pj;
-        psum += (float)pj;
-      }
-      l_run[j] = l_run[j] * alpha + psum;
-      m_run[j] = m_new;
+      for (int i = 0; i < 8; ++i)
+        pb[i] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sc[i >> 2][i & 3], p.scale_log2, -m_run[j]));
+      // the row sums come from the matrix unit too (a tile of ones as the "V" operand), so the
+      // denominator sums exactly the rounded weights the numerator uses
+      accl[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb, accl[j], 0, 0, 0);
 #pragma unroll
-      for (int dt = 0; dt < EPL; ++dt) {
-        acc[j][dt] *= alpha;
+      for (int dt = 0; dt < EPL; ++dt)
         acc[j][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pb, acc[j][dt], 0, 0, 0);
-      }
     }
   }
 
   // ---- results: column-owned, no merge across waves ----
   const int nch = (p.tile_base[tile + 1] - p.tile_base[tile]) / p.Hkv;
-  const size_t item = (size_t)p.item_first + blockIdx.x;
+  const size_t item = (size_t)item_id;
 #pragma unroll
   for (int j = 0; j < kNQ; ++j) {
-    float l = l_run[j];
-    l += __shfl_xor(l, 16);
-    l += __shfl_xor(l, 32);
+    const float l = accl[j][0];   // every row of the ones-tile product holds the column's sum
     const int col = (wave * kNQ + j) * 16 + c16;
     if (nch == 1) {
       if (cvalid[j]) {
@@ -317,6 +346,7 @@ static PrefillParams pf_params(vkv_pool* p, int32_t layer, const void* q, const 
   a.work = (const WorkItem*)(ws + p->pf.off_work);
   a.tiles = (const int32_t*)(ws + p->pf.off_tiles);
   a.tile_base = (const int32_t*)(ws + p->pf.off_tile_base);
+  a.order = (const int32_t*)(ws + p->pf.off_order);
   a.q = (const uint16_t*)q;
   a.table = table;
   a.part_acc = (float*)(ws + p->pf.off_acc);
@@ -364,9 +394,9 @@ extern "C" {
 int kv_prefill_plan(vkv_pool* p, const int32_t* ctx, const int32_t* q_len, int32_t S, uint64_t slice_bytes,
                     int32_t chunk_tokens, vkv_prefill_plan_info* info) {
   if (!p || !ctx || !q_len || S < 1) { set_error("kv_prefill_plan: bad argument"); return VKV_E_INVAL; }
-  if (chunk_tokens < kGroupTokens || chunk_tokens % kGroupTokens || chunk_tokens > kMaxChunkTokens) {
+  if (chunk_tokens < kGroupTokens || chunk_tokens % kGroupTokens || chunk_tokens > kMaxPrefillChunkTokens) {
     set_error("kv_prefill_plan: chunk_tokens must be a multiple of %d in [%d, %d]", kGroupTokens, kGroupTokens,
-              kMaxChunkTokens);
+              kMaxPrefillChunkTokens);
     return VKV_E_INVAL;
   }
   const int Hkv = p->cfg.num_kv_heads, D = p->cfg.head_dim, B = p->cfg.block_tokens, G = p->G;
@@ -423,7 +453,15 @@ int kv_prefill_plan(vkv_pool* p, const int32_t* ctx, const int32_t* q_len, int32
   pl.off_work = 256;
   pl.off_tiles = pl.off_work + n_items * sizeof(WorkItem);
   pl.off_tile_base = pl.off_tiles + n_tiles * 16;
-  pl.upload_bytes = pl.off_tile_base + (n_tiles + 1) * 4;
+  pl.off_order = pl.off_tile_base + (n_tiles + 1) * 4;
+  pl.upload_bytes = pl.off_order + n_items * 4;
+  // Workgroups start in grid order: the longest items of a slice go first so that the short ones fill
+  // the tail.  Results are stored by item id, so the order is invisible outside the kernel.
+  pl.order.resize(n_items);
+  for (size_t i = 0; i < n_items; ++i) pl.order[i] = (int32_t)i;
+  for (size_t sl = 0; sl + 1 < pl.slice_start.size(); ++sl)
+    std::stable_sort(pl.order.begin() + pl.slice_start[sl], pl.order.begin() + pl.slice_start[sl + 1],
+                     [&](int32_t a, int32_t b) { return pl.work[a].n_tokens > pl.work[b].n_tokens; });
   pl.off_ml = align_up(pl.upload_bytes, 256);
   pl.off_acc = align_up(pl.off_ml + n_items * kTileColumns * 2 * 4, 256);
   pl.total = align_up(pl.off_acc + n_items * kTileColumns * (uint64_t)D * 4, 256);
@@ -471,6 +509,7 @@ int kv_prefill_bind(vkv_pool* p, void* workspace, uint64_t workspace_bytes, void
   std::memcpy(h + p->pf.off_work, p->pf.work.data(), p->pf.work.size() * sizeof(WorkItem));
   std::memcpy(h + p->pf.off_tiles, p->pf.tiles.data(), p->pf.tiles.size() * 4);
   std::memcpy(h + p->pf.off_tile_base, p->pf.tile_base.data(), p->pf.tile_base.size() * 4);
+  std::memcpy(h + p->pf.off_order, p->pf.order.data(), p->pf.order.size() * 4);
   VKV_HIP(hipMemcpyAsync(workspace, h, p->pf.upload_bytes, hipMemcpyHostToDevice, (hipStream_t)stream));
   VKV_HIP(hipEventRecord(p->stage_ev, (hipStream_t)stream));
   p->stage_inflight = true;

@@ -47,6 +47,8 @@ def run_prefill(c, q, q_len, layer, slice_bytes, chunk_tokens, through_scheduler
     ("llama8b_small", 2, [4096] * 8, 2048, 8 << 20),
     ("llama70b_tp8_small", 3, [100, 1, 16, 700, 31, 32, 33, 2000, 8, 9, 10, 640], 256, 1 << 19),
     ("offline_batch_small", 4, [1000, 2, 129, 4096, 77, 512], 1024, 1 << 21),
+    # items longer than two 64-entry windows of block ids
+    ("llama70b_tp8_small", 5, [1500, 40, 8192, 3, 700, 2500, 64, 1, 900, 4000, 33, 256], 8192, 4 << 20),
 ])
 def test_prefill_matches_oracle(name, seed, q_lens, chunk, slice_bytes):
     from gpu_util import layout_of

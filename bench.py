@@ -63,6 +63,11 @@ def main():
     ap.add_argument("--concurrent-reclaim", action="store_true",
                     help="extra leg: rate-capped, chunked reclamation on a second stream while decode runs")
     ap.add_argument("--rate-cap", type=float, default=None, help="bytes/s for the concurrent leg")
+    ap.add_argument("--bursts", type=int, default=0,
+                    help="extra leg: this many online bursts (yield, reclaim, hold, return) at exponential "
+                         "inter-arrival times while decode runs continuously")
+    ap.add_argument("--burst-mean-s", type=float, default=0.2)
+    ap.add_argument("--burst-hold-ms", type=float, default=20.0)
     ap.add_argument("--prefill-leg", action="store_true",
                     help="extra leg: causal prefill of the newest --prefill-tokens tokens of every sequence")
     ap.add_argument("--prefill-tokens", type=int, default=2048)
@@ -87,6 +92,12 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    t_begin_run = time.time()
+
+    def progress(msg):
+        """Phase marker on stderr (stdout carries the one JSON line only)."""
+        print(f"[bench {time.time() - t_begin_run:7.1f}s] {msg}", file=sys.stderr, flush=True)
+
     wl = synth.workload(args.workload)
     g = wl.geom
     chunk_tokens = args.chunk_tokens or wl.chunk_tokens
@@ -98,7 +109,13 @@ def main():
     t_setup = time.time()
     st = synth.build_state(wl, args.seed, materialize_pool=False)
     pool_t = torch.empty(g.pool_elems, dtype=torch.int16, device=dev)
-    synth.fill_pool_torch(pool_t, g, args.seed)
+    progress(f"filling the {g.pool_bytes / 2**30:.0f} GiB pool on the device")
+    fill_step = 1 << 33                                   # elements per progress line (16 GiB)
+    for lo_e in range(0, g.pool_elems, fill_step):
+        hi_e = min(g.pool_elems, lo_e + fill_step)
+        synth.fill_pool_range_torch(pool_t, g, args.seed, lo_e, hi_e)
+        torch.cuda.synchronize()
+        progress(f"  filled {hi_e * 2 / 2**30:.0f} GiB")
     synth.poison_unused_slots(st, pool_t)
     q_all = torch.stack([torch.from_numpy(synth.query_bits(wl, args.seed, l).view(np.int16)) for l in range(L)]).to(dev)
     tables0 = torch.from_numpy(st.tables).to(dev)
@@ -141,12 +158,14 @@ def main():
         tables.copy_(tables0, non_blocking=True)
         return rs
 
+    progress("inputs resident; warm-up steps")
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
     if use_events:
         vkv.kv_profile_read(pool, 1 << 20)   # drop warm-up records
 
+    progress("timed steps")
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -197,6 +216,47 @@ def main():
         })
         vkv.kv_profile_enable(pool, 0)
 
+    progress("bandwidth yardsticks")
+    # ---- yardsticks: what the memory system gives a sequential read and the runtime's own copy
+    def timed_ms(fn, reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        fn(0)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for i in range(reps):
+            fn(i + 1)
+        e1.record(stream)
+        e1.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    pool_bytes = g.pool_elems * 2
+    sink = torch.zeros(256, dtype=torch.uint8, device=dev)
+    big = min(pool_bytes, 8 << 30) // 65536 * 65536
+    launch_sized = int(decode_bytes_layer / info.n_slices) // 65536 * 65536
+    n_regions = max(1, pool_bytes // launch_sized)
+    base_addr = pool_t.data_ptr()
+    read_big_ms = timed_ms(lambda i: vkv.kv_probe_read(base_addr, big, sink, stream), 4)
+    read_launch_ms = timed_ms(lambda i: vkv.kv_probe_read(base_addr + (i % n_regions) * launch_sized, launch_sized,
+                                                          sink, stream), 16)
+    cp_bytes = 1 << 30
+    cp_a = torch.empty(cp_bytes, dtype=torch.uint8, device=dev)
+    cp_b = torch.empty(cp_bytes, dtype=torch.uint8, device=dev)
+    copy_ms = timed_ms(lambda i: vkv.kv_probe_copy(cp_b, cp_a, cp_bytes, stream), 4)
+    del cp_a, cp_b
+    ceilings = {
+        "sequential_read_GBps": round(big / read_big_ms / 1e6, 1), "sequential_read_bytes": int(big),
+        "sequential_read_at_launch_size_GBps": round(launch_sized / read_launch_ms / 1e6, 1),
+        "launch_size_bytes": int(launch_sized),
+        "runtime_copy_traffic_GBps": round(2 * cp_bytes / copy_ms / 1e6, 1), "copy_bytes": cp_bytes,
+    }
+    if roofline is not None:
+        roofline["frac_of_read_ceiling_at_launch_size"] = round(
+            roofline["achieved"] / ceilings["sequential_read_at_launch_size_GBps"], 4)
+    if roofline_reclaim is not None:
+        roofline_reclaim["frac_of_runtime_copy"] = round(
+            roofline_reclaim["achieved"] / ceilings["runtime_copy_traffic_GBps"], 4)
+
+    progress("decode-only and reclaim-only legs")
     # ---- separate legs: decode only, reclaim only (wall clock, no launch events) ----
     reps = max(3, args.steps)
     decode_pass()
@@ -229,6 +289,7 @@ def main():
         "reclaim_blocks_moved": int(rs.blocks_moved),
     })
 
+    progress("yield injections")
     # ---- end-to-end yield latency: request at a random instant, until compute is off the GPU
     if args.yield_injections > 0:
         rng = np.random.default_rng(args.seed)
@@ -268,6 +329,7 @@ def main():
                       "yield_latency_us_p99": round(percentile(lat, 99), 1),
                       "yield_latency_us_max": round(max(lat), 1), "yield_injections": len(lat)})
 
+    progress("optional legs")
     # ---- optional: reclamation under a rate cap on a second stream while decode keeps running
     if args.concurrent_reclaim:
         cap = args.rate_cap or wl.rate_cap or 20e9
@@ -312,6 +374,106 @@ def main():
             "concurrent_decode_GBps": round((n_b - n_a) * decode_bytes_layer / (t_b - t_a) / 1e9, 1),
         })
 
+    # ---- optional: online bursts against a continuous offline decode loop --------------------
+    # Each burst: yield request -> offline compute off the GPU -> the top range emptied and handed
+    # over -> the online tenant holds it -> range returned, offline resumes (its KV "grows back":
+    # the bookkeeping is rewound; the sources were left intact by the copy).
+    if args.bursts > 0:
+        brng = np.random.default_rng(args.seed + 1)
+        arrivals = np.cumsum(brng.exponential(args.burst_mean_s, size=args.bursts))
+        decode_stream, copy_stream = torch.cuda.Stream(), torch.cuda.Stream()
+        torch.cuda.synchronize()
+        stop = threading.Event()
+        cv = threading.Condition()
+        gate = {"want_pause": False, "paused": False}    # both only change under cv
+        layers_done = [0]
+
+        def offline():
+            layer, cur = 0, 0
+            while not stop.is_set():
+                with cv:
+                    while gate["want_pause"] and not stop.is_set():
+                        gate["paused"] = True          # nothing of ours is on the GPU: every call below
+                        cv.notify_all()                # returns only after its launches have drained
+                        cv.wait(0.05)
+                    gate["paused"] = False
+                s_, cur = vkv.kv_attn_run_layer(pool, layer, cur, q_all[layer], tables, ws, out[layer],
+                                                max_inflight=args.max_inflight, stream=decode_stream)
+                if s_ != vkv.VKV_YIELDED:
+                    layers_done[0] += 1
+                    layer, cur = (layer + 1) % L, 0
+            decode_stream.synchronize()
+
+        def give_back():
+            vkv.kv_pool_return_range(pool, lo, hi)
+            vkv.kv_pool_free(pool, dst_ids)
+            vkv.kv_pool_adopt(pool, src_ids)
+            with torch.cuda.stream(copy_stream):
+                tables.copy_(tables0)
+            copy_stream.synchronize()
+
+        # one untimed reclamation on the two new streams (their first use creates queues)
+        progress("burst leg: untimed reclamation on the new streams")
+        vkv.kv_reclaim_range(pool, lo, hi, tables, remap, chunk_bytes=rc_chunk, copy_stream=copy_stream,
+                             decode_stream=decode_stream)
+        give_back()
+        progress("burst leg: offline loop starts")
+        th = threading.Thread(target=offline)
+        t_start = time.perf_counter()
+        th.start()
+        to_idle, to_released, paused = [], [], 0.0
+        for a in arrivals:
+            now = time.perf_counter() - t_start
+            if a > now:
+                time.sleep(a - now)
+            t_arr = max(a, now) + t_start     # a burst that finds the previous one in service waits its turn
+            t_req = time.perf_counter()
+            verbose = len(to_released) < 3
+            if verbose:
+                progress(f"  burst {len(to_released)}: yield requested after {layers_done[0]} layers")
+            with cv:
+                gate["want_pause"] = True
+            vkv.kv_yield_request(pool)
+            with cv:
+                while not gate["paused"]:
+                    cv.wait()
+            t_idle = time.perf_counter()
+            if verbose:
+                progress("    offline compute is off the GPU; reclaiming")
+            vkv.kv_reclaim_range(pool, lo, hi, tables, remap, chunk_bytes=rc_chunk, copy_stream=copy_stream,
+                                 decode_stream=decode_stream)
+            t_rel = time.perf_counter()
+            to_idle.append((t_idle - t_req) * 1e3)
+            to_released.append((t_rel - min(t_arr, t_req)) * 1e3)
+            if verbose:
+                progress("    range handed over; online tenant holds it")
+            time.sleep(args.burst_hold_ms * 1e-3)
+            give_back()
+            vkv.kv_yield_clear(pool)
+            paused += time.perf_counter() - t_req
+            with cv:
+                gate["want_pause"] = False
+                cv.notify_all()
+            if len(to_released) % 20 == 0:
+                progress(f"  burst {len(to_released)} of {args.bursts}")
+        stop.set()
+        th.join()
+        torch.cuda.synchronize()
+        total_s = time.perf_counter() - t_start
+        extra.update({
+            "bursts": int(args.bursts), "burst_mean_interarrival_s": args.burst_mean_s,
+            "burst_hold_ms": args.burst_hold_ms, "burst_run_s": round(total_s, 2),
+            "burst_reclaimed_bytes": int((hi - lo) * g.block_bytes), "burst_moved_bytes": int(rs.bytes_moved),
+            "burst_yield_to_idle_ms_p50": round(percentile(to_idle, 50), 3),
+            "burst_yield_to_idle_ms_p99": round(percentile(to_idle, 99), 3),
+            "burst_arrival_to_released_ms_p50": round(percentile(to_released, 50), 3),
+            "burst_arrival_to_released_ms_p99": round(percentile(to_released, 99), 3),
+            "burst_arrival_to_released_ms_max": round(max(to_released), 3),
+            "burst_offline_paused_frac": round(paused / total_s, 4),
+            "burst_decode_GBps_whole_run": round(layers_done[0] * decode_bytes_layer / total_s / 1e9, 1),
+            "burst_decode_GBps_while_running": round(layers_done[0] * decode_bytes_layer / (total_s - paused) / 1e9, 1),
+        })
+
     # ---- optional: preemptible causal prefill over the same pool (MFMA-bound) -------------
     if args.prefill_leg:
         q_len = np.minimum(st.ctx_len, args.prefill_tokens).astype(np.int32)
@@ -350,6 +512,7 @@ def main():
         })
         del pws, pq, pout
 
+    progress("CPU oracle baseline")
     # ---- the CPU oracle on a bounded sample of the same workload --------------------
     cpu_baseline = None
     if not args.no_cpu_baseline:
@@ -371,6 +534,7 @@ def main():
         "step_bytes": step_bytes, "decode_bytes": decode_bytes, "reclaim_traffic_bytes": reclaim_traffic,
         "setup_s": round(setup_s, 1),
         "roofline": roofline, "roofline_reclaim": roofline_reclaim, "cpu_baseline": cpu_baseline,
+        "ceilings": ceilings,
     }
     line.update(extra)
     print(json.dumps(line), flush=True)

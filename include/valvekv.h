@@ -405,6 +405,24 @@ int kv_profile_enable(vkv_pool* pool, int32_t max_records);
  * order) to out_host, their count to *n_out, and restarts recording at zero. */
 int kv_profile_read(vkv_pool* pool, vkv_profile_record* out_host, int32_t cap, int32_t* n_out);
 
+/* ---- bandwidth yardsticks ---------------------------------------------------
+ * Not part of the method: the attention and relocation kernels are bound by
+ * HBM bandwidth, and these two calls measure what the memory system gives the
+ * simplest patterns on the same device, so a kernel can be quoted against the
+ * reachable rate as well as against the data-sheet peak.  The caller times
+ * them (events on `stream`). */
+
+/* Launches a read-only kernel that streams src_dev[0, bytes) once,
+ * sequentially, 64 KiB per workgroup.  sink_dev: 256 bytes of device scratch
+ * (written only if the xor of the data equals one fixed 128-bit value).
+ * bytes: positive multiple of 16; both pointers 16-byte aligned.
+ * Errors: VKV_E_INVAL, VKV_E_HIP. */
+int kv_probe_read(const void* src_dev, uint64_t bytes, void* sink_dev, void* stream);
+
+/* Enqueues the runtime's own device-to-device copy of bytes bytes (regions must
+ * not overlap).  Errors: VKV_E_INVAL, VKV_E_HIP. */
+int kv_probe_copy(void* dst_dev, const void* src_dev, uint64_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

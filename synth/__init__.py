@@ -17,6 +17,7 @@ from .workload import (  # noqa: F401
     hash_bf16_bits_torch,
     pool_bits_for_blocks,
     fill_pool_torch,
+    fill_pool_range_torch,
     query_bits,
     poison_unused_slots,
     unused_slot_spans,

@@ -235,17 +235,23 @@ def pool_bits_for_blocks(geom: Geometry, seed: int, block_ids: Sequence[int]) ->
     return out
 
 
-def fill_pool_torch(pool_i16, geom: Geometry, seed: int, chunk_elems: int = 1 << 26) -> None:
-    """Fill a flat int16 torch tensor of pool_elems elements in place (device or host)."""
+def fill_pool_range_torch(pool_i16, geom: Geometry, seed: int, first: int, last: int,
+                          chunk_elems: int = 1 << 26) -> None:
+    """Fill elements [first, last) of a flat int16 torch tensor of pool_elems elements in place."""
     import torch
 
-    n = geom.pool_elems
-    assert pool_i16.numel() >= n and pool_i16.dtype == torch.int16
+    assert pool_i16.numel() >= geom.pool_elems and pool_i16.dtype == torch.int16
+    assert 0 <= first <= last <= geom.pool_elems
     flat = pool_i16.view(-1)
-    for lo in range(0, n, chunk_elems):
-        hi = min(n, lo + chunk_elems)
+    for lo in range(first, last, chunk_elems):
+        hi = min(last, lo + chunk_elems)
         idx = torch.arange(lo, hi, dtype=torch.int64, device=flat.device)
         flat[lo:hi] = hash_bf16_bits_torch(idx, seed, STREAM_POOL)
+
+
+def fill_pool_torch(pool_i16, geom: Geometry, seed: int, chunk_elems: int = 1 << 26) -> None:
+    """Fill a flat int16 torch tensor of pool_elems elements in place (device or host)."""
+    fill_pool_range_torch(pool_i16, geom, seed, 0, geom.pool_elems, chunk_elems)
 
 
 def query_bits(wl: Workload, seed: int, layer: int) -> np.ndarray:

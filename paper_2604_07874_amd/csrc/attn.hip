@@ -52,6 +52,7 @@ struct AttnParams {
   float* part_acc;           // [n_items][G][D]
   float* part_ml;            // [n_items][G][2]
   const int32_t* seq_base;   // [S+1] first item of each sequence
+  const int32_t* order;      // [n_items] launch order: inside a slice, items by falling token count
   int32_t* done;             // [S][Hkv] chunks finished in the current layer
   float* out;                // [S][Hq][D]
   uint32_t* err;             // workspace header word 0
@@ -95,7 +96,8 @@ __global__ __launch_bounds__(256, 2) void paged_decode_attn_slice_kernel(const A
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int c16 = lane & 15, kg = lane >> 4;
 
-  const WorkItem it = p.work[p.item_first + blockIdx.x];
+  const int item_id = p.order[p.item_first + blockIdx.x];   // workgroups start in grid order: longest items first
+  const WorkItem it = p.work[item_id];
   const int ntok = it.n_tokens;
   const int ngroups = (ntok + kGroupTokens - 1) / kGroupTokens;
   const int G = p.G;
@@ -261,7 +263,7 @@ __global__ __launch_bounds__(256, 2) void paged_decode_attn_slice_kernel(const A
     }
   }
   __syncthreads();
-  const size_t item = (size_t)p.item_first + blockIdx.x;
+  const size_t item = (size_t)item_id;
   const int base = p.seq_base[it.seq];
   const int nch = (p.seq_base[it.seq + 1] - base) / p.Hkv;   // chunks of this sequence
   float* orow = p.out + ((size_t)it.seq * p.Hq + (size_t)it.kv_head * G) * D;
@@ -369,6 +371,7 @@ static int launch_slice(vkv_pool* p, int32_t layer, int32_t slice, const void* q
   a.part_acc = (float*)(ws + p->ws.part_acc);
   a.part_ml = (float*)(ws + p->ws.part_ml);
   a.seq_base = (const int32_t*)(ws + p->ws.seq_base);
+  a.order = (const int32_t*)(ws + p->ws.order);
   a.done = (int32_t*)(ws + p->ws.done);
   a.out = (float*)out;
   a.err = (uint32_t*)(ws + p->ws.header);
@@ -523,6 +526,16 @@ int kv_attn_plan(vkv_pool* p, const int32_t* ctx, int32_t S, uint64_t slice_byte
   max_slice = std::max(max_slice, acc);
   starts.push_back((int32_t)work.size());
 
+  // Workgroups start in grid order.  Inside a slice the longest items go first, so the short
+  // ones (ragged ends of sequences) fill the tail of the launch; equal items keep the plan's
+  // order (the kv heads of one chunk stay neighbours and read one slab together).  Results are
+  // stored by item id, so the launch order is invisible outside the kernel.
+  std::vector<int32_t> order(work.size());
+  for (size_t i = 0; i < order.size(); ++i) order[i] = (int32_t)i;
+  for (size_t sl = 0; sl + 1 < starts.size(); ++sl)
+    std::stable_sort(order.begin() + starts[sl], order.begin() + starts[sl + 1],
+                     [&](int32_t a, int32_t b) { return work[a].n_tokens > work[b].n_tokens; });
+  p->order.swap(order);
   p->work.swap(work);
   p->slice_start.swap(starts);
   p->seq_base.swap(seq_base);
@@ -565,6 +578,7 @@ int kv_attn_bind(vkv_pool* p, void* workspace, uint64_t workspace_bytes, void* s
   std::memset(h, 0, p->ws.upload_bytes);   // flag word and per-(sequence, kv head) counters start at zero
   std::memcpy(h + p->ws.work, p->work.data(), p->work.size() * sizeof(WorkItem));
   std::memcpy(h + p->ws.seq_base, p->seq_base.data(), p->seq_base.size() * 4);
+  std::memcpy(h + p->ws.order, p->order.data(), p->order.size() * 4);
   VKV_HIP(hipMemcpyAsync(workspace, h, p->ws.upload_bytes, hipMemcpyHostToDevice, (hipStream_t)stream));
   VKV_HIP(hipEventRecord(p->stage_ev, (hipStream_t)stream));
   p->stage_inflight = true;

@@ -187,6 +187,18 @@ int kv_attn_run_layer(vkv_pool* pool, int32_t layer, int32_t* cursor_slice,
                       void* workspace, void* out_f32, float softmax_scale,
                       int32_t max_inflight, void* stream);
 
+/* With enable != 0 the slice schedulers (kv_attn_run_layer, kv_prefill_run_layer)
+ * send every other slice of a layer to a second stream owned by the pool
+ * (created on first use, default priority), forked from and joined back into the
+ * caller's stream inside the same call: the head of one launch fills the
+ * compute units that the tail of the previous one leaves idle.  Ordering seen
+ * by the caller is unchanged (work enqueued on `stream` before the call
+ * precedes every slice; work enqueued after it follows every slice), results
+ * are bit-identical, and at most max_inflight launches are unfinished as
+ * before; it takes effect when max_inflight >= 2.  Off by default.  Decode
+ * thread only. */
+int kv_sched_set_overlap(vkv_pool* pool, int32_t enable);
+
 /* Yield flag (the online tenant's "busy" edge of Section 4.2).  Thread-safe. */
 int kv_yield_request(vkv_pool* pool);
 int kv_yield_clear(vkv_pool* pool);

@@ -25,7 +25,7 @@ __all__ = [
     "kv_prefill_merge", "kv_prefill_run_layer", "kv_prefill_check", "VKV_PROF_PREFILL", "VKV_PROF_PREFILL_MERGE",
     "kv_select_handles", "kv_invalidate_handles", "MiadConfig", "MiadStep", "kv_miad_init", "kv_miad_destroy",
     "kv_miad_observe", "kv_gate_init", "kv_gate_destroy", "kv_gate_online_busy", "kv_gate_online_idle",
-    "kv_gate_poll", "kv_gate_stats", "kv_probe_read", "kv_probe_copy",
+    "kv_gate_poll", "kv_gate_stats", "kv_probe_read", "kv_probe_copy", "kv_sched_set_overlap",
 ]
 
 VKV_OK, VKV_YIELDED = 0, 1
@@ -141,6 +141,7 @@ _sigs = {
     "kv_gate_stats": (C.c_int, [_P, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
     "kv_profile_enable": (C.c_int, [_P, C.c_int32]),
     "kv_profile_read": (C.c_int, [_P, _P, C.c_int32, _I32P]),
+    "kv_sched_set_overlap": (C.c_int, [_P, C.c_int32]),
     "kv_probe_read": (C.c_int, [_P, C.c_uint64, _P, _P]),
     "kv_probe_copy": (C.c_int, [_P, _P, C.c_uint64, _P]),
 }
@@ -323,6 +324,10 @@ def kv_profile_read(pool, cap: int) -> np.ndarray:
     n = C.c_int32(0)
     _check(lib.kv_profile_read(pool, buf.ctypes.data, cap, C.byref(n)))
     return buf[:n.value]
+
+
+def kv_sched_set_overlap(pool, enable: bool):
+    _check(lib.kv_sched_set_overlap(pool, 1 if enable else 0))
 
 
 # ---- bandwidth yardsticks ---------------------------------------------------------

@@ -413,8 +413,13 @@ static int check_slice_args(vkv_pool* p, int32_t layer, const void* q, const int
 // Slice scheduler shared by decode and prefill: issues slices *cursor .. n_slices-1 through
 // `launch`, then `tail` (if any), keeping at most max_inflight launches unfinished; the ring of
 // events persists across calls.  Stops at a slice boundary when the yield flag is set.
+// With overlap on, odd slices go to a second stream the pool owns (forked from and joined back
+// into the caller's stream inside this call), so the workgroups of the next slice fill the
+// compute units the tail of the previous one leaves idle; slices of one layer are independent
+// (results are merged through per-item partials), so their order does not matter.
 int run_slices(vkv_pool* p, int32_t* cursor, int32_t n_slices, int32_t max_inflight, hipStream_t hs,
-               const char* who, const std::function<int(int32_t)>& launch, const std::function<int()>& tail) {
+               const char* who, const std::function<int(int32_t, hipStream_t)>& launch,
+               const std::function<int()>& tail) {
   if (!cursor || *cursor < 0 || *cursor > n_slices || max_inflight < 1 || max_inflight > kMaxInflight) {
     set_error("%s: bad cursor or max_inflight", who);
     return VKV_E_INVAL;
@@ -442,26 +447,49 @@ int run_slices(vkv_pool* p, int32_t* cursor, int32_t n_slices, int32_t max_infli
     }
     return VKV_OK;
   };
-  auto track = [&]() -> int {
-    VKV_HIP(hipEventRecord(p->inflight_ev[(p->inflight_head + p->inflight_count) % max_inflight], hs));
+  auto track = [&](hipStream_t on) -> int {
+    VKV_HIP(hipEventRecord(p->inflight_ev[(p->inflight_head + p->inflight_count) % max_inflight], on));
     ++p->inflight_count;
+    return VKV_OK;
+  };
+  const bool two = p->overlap && max_inflight >= 2 && n_slices - *cursor >= 2;
+  bool aux_used = false;
+  if (two) {
+    if (!p->aux_stream) VKV_HIP(hipStreamCreateWithFlags(&p->aux_stream, hipStreamNonBlocking));
+    if (!p->fork_ev) VKV_HIP(hipEventCreateWithFlags(&p->fork_ev, hipEventDisableTiming));
+    if (!p->join_ev) VKV_HIP(hipEventCreateWithFlags(&p->join_ev, hipEventDisableTiming));
+    // the second stream starts after everything the caller has enqueued so far (q, tables, the plan upload)
+    VKV_HIP(hipEventRecord(p->fork_ev, hs));
+    VKV_HIP(hipStreamWaitEvent(p->aux_stream, p->fork_ev, 0));
+  }
+  // later work on the caller's stream (the merge, the next layer) waits for the second stream's slices
+  auto join = [&]() -> int {
+    if (aux_used) {
+      VKV_HIP(hipEventRecord(p->join_ev, p->aux_stream));
+      VKV_HIP(hipStreamWaitEvent(hs, p->join_ev, 0));
+      aux_used = false;
+    }
     return VKV_OK;
   };
   for (int32_t s = *cursor; s < n_slices; ++s) {
     if (p->yield_flag.load(std::memory_order_acquire)) {
       st = drain();
       if (st != VKV_OK) return st;
+      if ((st = join()) != VKV_OK) return st;
       *cursor = s;
       return VKV_YIELDED;
     }
+    const hipStream_t on = (two && (s & 1)) ? p->aux_stream : hs;
     if ((st = admit()) != VKV_OK) return st;
-    if ((st = launch(s)) != VKV_OK) return st;
-    if ((st = track()) != VKV_OK) return st;
+    if ((st = launch(s, on)) != VKV_OK) return st;
+    if ((st = track(on)) != VKV_OK) return st;
+    if (on != hs) aux_used = true;
   }
+  if ((st = join()) != VKV_OK) return st;
   if (tail && *cursor < n_slices + 1) {
     if ((st = admit()) != VKV_OK) return st;
     if ((st = tail()) != VKV_OK) return st;
-    if ((st = track()) != VKV_OK) return st;
+    if ((st = track(hs)) != VKV_OK) return st;
   }
   *cursor = n_slices;
   return VKV_OK;
@@ -616,8 +644,16 @@ int kv_attn_run_layer(vkv_pool* p, int32_t layer, int32_t* cursor, const void* q
   const int32_t n_slices = (int32_t)p->slice_start.size() - 1;
   hipStream_t hs = (hipStream_t)stream;
   return run_slices(p, cursor, n_slices, max_inflight, hs, "kv_attn_run_layer",
-                    [&](int32_t s) { return launch_slice(p, layer, s, q, table, max_blk, workspace, out, scale, hs); },
+                    [&](int32_t s, hipStream_t on) {
+                      return launch_slice(p, layer, s, q, table, max_blk, workspace, out, scale, on);
+                    },
                     nullptr);
+}
+
+int kv_sched_set_overlap(vkv_pool* p, int32_t enable) {
+  if (!p) { set_error("kv_sched_set_overlap: null pool"); return VKV_E_INVAL; }
+  p->overlap = enable != 0;
+  return VKV_OK;
 }
 
 }  // extern "C"

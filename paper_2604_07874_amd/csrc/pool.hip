@@ -120,6 +120,9 @@ int kv_pool_destroy(vkv_pool* p) {
   if (p->stage_ev) (void)hipEventDestroy(p->stage_ev);
   if (p->remap_ev) (void)hipEventDestroy(p->remap_ev);
   if (p->grace_ev) (void)hipEventDestroy(p->grace_ev);
+  if (p->fork_ev) (void)hipEventDestroy(p->fork_ev);
+  if (p->join_ev) (void)hipEventDestroy(p->join_ev);
+  if (p->aux_stream) (void)hipStreamDestroy(p->aux_stream);
   for (auto& e : p->inflight_ev)
     if (e) (void)hipEventDestroy(e);
   for (auto& e : p->prof_ev) (void)hipEventDestroy(e);

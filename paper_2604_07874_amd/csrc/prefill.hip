@@ -543,7 +543,9 @@ int kv_prefill_run_layer(vkv_pool* p, int32_t layer, int32_t* cursor, const void
   if (st != VKV_OK) return st;
   hipStream_t hs = (hipStream_t)stream;
   return run_slices(p, cursor, (int32_t)p->pf.slice_start.size() - 1, max_inflight, hs, "kv_prefill_run_layer",
-                    [&](int32_t s) { return pf_launch_slice(p, layer, s, q, table, max_blk, workspace, out, scale, hs); },
+                    [&](int32_t s, hipStream_t on) {
+                      return pf_launch_slice(p, layer, s, q, table, max_blk, workspace, out, scale, on);
+                    },
                     [&]() { return pf_launch_merge(p, workspace, out, hs); });
 }
 

@@ -122,6 +122,10 @@ struct vkv_pool {
   // ring of events behind launches that may still be running; it persists across
   // kv_attn_run_layer calls so the host never runs more than max_inflight launches ahead
   hipEvent_t inflight_ev[vkv::kMaxInflight] = {};
+  // second stream for overlapping consecutive slices of one layer (created on first use)
+  bool overlap = false;
+  hipStream_t aux_stream = nullptr;
+  hipEvent_t fork_ev = nullptr, join_ev = nullptr;
   int inflight_head = 0, inflight_count = 0, inflight_cap = 0;
   std::atomic<int> yield_flag{0};
 
@@ -162,7 +166,7 @@ struct ProfScope {
 
 // Slice scheduler shared by decode and prefill (attn.hip).
 int run_slices(vkv_pool* p, int32_t* cursor, int32_t n_slices, int32_t max_inflight, hipStream_t hs, const char* who,
-               const std::function<int(int32_t)>& launch, const std::function<int()>& tail);
+               const std::function<int(int32_t, hipStream_t)>& launch, const std::function<int()>& tail);
 
 // Host-side relocation plan; see kv_reclaim_plan.
 int plan_relocation(const vkv_pool* p, int32_t lo, int32_t hi,

@@ -66,3 +66,33 @@ def test_small_configs(name):
         check_attention(c, [wl.geom.num_layers - 1], chunk_tokens=128, slice_bytes=1 << 20)
     finally:
         c.close()
+
+
+def test_overlapped_slices_keep_stream_order_and_bits():
+    """With every other slice on the pool's second stream, work enqueued on the caller's stream
+    before the call still precedes all slices and work enqueued after it follows all of them."""
+    from gpu_util import DeviceCase
+    c = DeviceCase(synth.workload("stress_small"), 11)
+    try:
+        g, vkv = c.wl.geom, c.vkv
+        info = c.plan(slice_bytes=1 << 19)
+        assert info.n_slices >= 8
+        q, q_t = c.q_dev(1)
+        full = c.attention(1, q_t)
+        vkv.kv_sched_set_overlap(c.pool, True)
+        side = torch.cuda.Stream()
+        out = torch.empty((c.wl.num_seqs, g.num_q_heads, g.head_dim), dtype=torch.float32, device="cuda:0")
+        torch.cuda.synchronize()
+        for rep in range(3):
+            with torch.cuda.stream(side):
+                q_late = torch.zeros_like(q_t)
+                q_late.copy_(q_t)                     # the query arrives on the stream just before the call
+                out.fill_(float("nan"))
+                st, cur = vkv.kv_attn_run_layer(c.pool, 1, 0, q_late, c.tables_t, c.ws, out, max_inflight=4, stream=side)
+                assert (st, cur) == (vkv.VKV_OK, info.n_slices)
+                got = out.clone()                     # read on the same stream right after, no host wait between
+            side.synchronize()
+            assert np.array_equal(got.cpu().numpy(), full), rep
+        vkv.kv_attn_check(c.pool, c.ws, side)
+    finally:
+        c.close()

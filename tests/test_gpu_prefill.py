@@ -80,10 +80,12 @@ def test_prefill_matches_oracle(name, seed, q_lens, chunk, slice_bytes):
         c.close()
 
 
-def test_prefill_yield_resume_and_reclaim_keep_the_bits():
+@pytest.mark.parametrize("overlap", [False, True])
+def test_prefill_yield_resume_and_reclaim_keep_the_bits(overlap):
     c, q, q_start, q_len = make("stress_small", 6, [700, 64, 2048, 300, 1, 1500, 90, 1024, 33, 512])
     try:
         vkv, g = c.vkv, c.wl.geom
+        vkv.kv_sched_set_overlap(c.pool, overlap)
         info, full, (ws, q_t) = run_prefill(c, q, q_len, 1, 1 << 20, 512)
         assert info.n_slices >= 6
         out = torch.empty((info.total_q, g.num_q_heads, g.head_dim), dtype=torch.float32, device="cuda:0")

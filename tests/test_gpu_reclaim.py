@@ -152,10 +152,12 @@ def test_attention_unchanged_by_reclaim_and_poison():
         c.close()
 
 
-def test_yield_resume_is_bit_identical_at_every_slice():
+@pytest.mark.parametrize("overlap", [False, True])
+def test_yield_resume_is_bit_identical_at_every_slice(overlap):
     c = make_case("offline_batch_small", 8)
     try:
         g, vkv = c.wl.geom, c.vkv
+        vkv.kv_sched_set_overlap(c.pool, overlap)   # every other slice on the pool's second stream
         info = c.plan(slice_bytes=1 << 20)
         assert info.n_slices >= 8
         q, q_t = c.q_dev(0)

@@ -195,8 +195,11 @@ int kv_attn_run_layer(vkv_pool* pool, int32_t layer, int32_t* cursor_slice,
  * by the caller is unchanged (work enqueued on `stream` before the call
  * precedes every slice; work enqueued after it follows every slice), results
  * are bit-identical, and at most max_inflight launches are unfinished as
- * before; it takes effect when max_inflight >= 2.  Off by default.  Decode
- * thread only. */
+ * before; it takes effect when max_inflight >= 2.  Off by default.  The first
+ * enabling call creates the stream (the device of the pool must be current);
+ * make it before a second thread starts using the pool: kv_reclaim_range's
+ * grace wait covers this stream too and reads its handle.
+ * Errors: VKV_E_INVAL, VKV_E_HIP. */
 int kv_sched_set_overlap(vkv_pool* pool, int32_t enable);
 
 /* Yield flag (the online tenant's "busy" edge of Section 4.2).  Thread-safe. */

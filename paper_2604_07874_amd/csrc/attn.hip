@@ -452,12 +452,9 @@ int run_slices(vkv_pool* p, int32_t* cursor, int32_t n_slices, int32_t max_infli
     ++p->inflight_count;
     return VKV_OK;
   };
-  const bool two = p->overlap && max_inflight >= 2 && n_slices - *cursor >= 2;
+  const bool two = p->overlap && p->aux_stream && max_inflight >= 2 && n_slices - *cursor >= 2;
   bool aux_used = false;
   if (two) {
-    if (!p->aux_stream) VKV_HIP(hipStreamCreateWithFlags(&p->aux_stream, hipStreamNonBlocking));
-    if (!p->fork_ev) VKV_HIP(hipEventCreateWithFlags(&p->fork_ev, hipEventDisableTiming));
-    if (!p->join_ev) VKV_HIP(hipEventCreateWithFlags(&p->join_ev, hipEventDisableTiming));
     // the second stream starts after everything the caller has enqueued so far (q, tables, the plan upload)
     VKV_HIP(hipEventRecord(p->fork_ev, hs));
     VKV_HIP(hipStreamWaitEvent(p->aux_stream, p->fork_ev, 0));
@@ -652,6 +649,13 @@ int kv_attn_run_layer(vkv_pool* p, int32_t layer, int32_t* cursor, const void* q
 
 int kv_sched_set_overlap(vkv_pool* p, int32_t enable) {
   if (!p) { set_error("kv_sched_set_overlap: null pool"); return VKV_E_INVAL; }
+  if (p->broken) { set_error("kv_sched_set_overlap: pool unusable after a HIP failure"); return VKV_E_HIP; }
+  if (enable) {
+    // created here, not on first use: the memory thread reads the handle during its grace wait
+    if (!p->aux_stream) VKV_HIP(hipStreamCreateWithFlags(&p->aux_stream, hipStreamNonBlocking));
+    if (!p->fork_ev) VKV_HIP(hipEventCreateWithFlags(&p->fork_ev, hipEventDisableTiming));
+    if (!p->join_ev) VKV_HIP(hipEventCreateWithFlags(&p->join_ev, hipEventDisableTiming));
+  }
   p->overlap = enable != 0;
   return VKV_OK;
 }

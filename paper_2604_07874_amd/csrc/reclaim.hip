@@ -205,6 +205,13 @@ int kv_reclaim_range(vkv_pool* p, int32_t lo, int32_t hi, int32_t* tables, int64
       if (he != hipSuccess) return fail(hip_fail(he, "hipEventRecord"));
       he = hipEventSynchronize(p->grace_ev);
       if (he != hipSuccess) return fail(hip_fail(he, "hipEventSynchronize"));
+      if (p->aux_stream) {
+        // slices the scheduler sent to the pool's second stream are in the same position
+        he = hipEventRecord(p->grace_ev, p->aux_stream);
+        if (he != hipSuccess) return fail(hip_fail(he, "hipEventRecord"));
+        he = hipEventSynchronize(p->grace_ev);
+        if (he != hipSuccess) return fail(hip_fail(he, "hipEventSynchronize"));
+      }
     }
   }
 

@@ -263,12 +263,14 @@ def test_rate_cap_is_respected():
         c.close()
 
 
-def test_rate_capped_reclaim_while_decode_runs_on_another_stream():
+@pytest.mark.parametrize("overlap", [False, True])
+def test_rate_capped_reclaim_while_decode_runs_on_another_stream(overlap):
     """The offline-batch shape's scenario: decode keeps running on its stream (its own host thread)
     while the range is emptied in small launches under a rate cap on a second stream."""
     c = make_case("offline_batch_small", 12, occupancy=0.8)
     try:
         g, vkv = c.wl.geom, c.vkv
+        vkv.kv_sched_set_overlap(c.pool, overlap)   # before the second thread exists
         orc = oracle_for(c)
         info = c.plan(slice_bytes=1 << 20)
         L = g.num_layers

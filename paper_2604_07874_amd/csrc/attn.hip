@@ -46,13 +46,12 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 struct AttnParams {
   const uint16_t* pool;      // pool base + layer offset (elements)
-  const WorkItem* work;      // device
+  const WorkItem* work;      // device; in launch order: inside a slice, items by falling token count
   const uint16_t* q;         // [S][Hq][D]
   const int32_t* table;      // [rows][max_blk]
   float* part_acc;           // [n_items][G][D]
   float* part_ml;            // [n_items][G][2]
   const int32_t* seq_base;   // [S+1] first item of each sequence
-  const int32_t* order;      // [n_items] launch order: inside a slice, items by falling token count
   int32_t* done;             // [S][Hkv] chunks finished in the current layer
   float* out;                // [S][Hq][D]
   uint32_t* err;             // workspace header word 0
@@ -61,6 +60,7 @@ struct AttnParams {
   int32_t item_first;
   int32_t max_blk;
   int32_t Hq, Hkv, G, NB;
+  int32_t chunk_blocks;      // blocks per full chunk (chunk_tokens / 16)
   float scale_log2;          // softmax scale * log2(e)
 };
 
@@ -96,8 +96,7 @@ __global__ __launch_bounds__(256, 2) void paged_decode_attn_slice_kernel(const A
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int c16 = lane & 15, kg = lane >> 4;
 
-  const int item_id = p.order[p.item_first + blockIdx.x];   // workgroups start in grid order: longest items first
-  const WorkItem it = p.work[item_id];
+  const WorkItem it = p.work[p.item_first + blockIdx.x];   // workgroups start in grid order: longest items first
   const int ntok = it.n_tokens;
   const int ngroups = (ntok + kGroupTokens - 1) / kGroupTokens;
   const int G = p.G;
@@ -263,8 +262,9 @@ __global__ __launch_bounds__(256, 2) void paged_decode_attn_slice_kernel(const A
     }
   }
   __syncthreads();
-  const size_t item = (size_t)item_id;
   const int base = p.seq_base[it.seq];
+  // item id in plan order (sequence, chunk, kv head): partial results are stored under it
+  const size_t item = (size_t)base + (size_t)(it.first_block / p.chunk_blocks) * p.Hkv + it.kv_head;
   const int nch = (p.seq_base[it.seq + 1] - base) / p.Hkv;   // chunks of this sequence
   float* orow = p.out + ((size_t)it.seq * p.Hq + (size_t)it.kv_head * G) * D;
   for (int e = threadIdx.x; e < G * D; e += 256) {
@@ -371,7 +371,7 @@ static int launch_slice(vkv_pool* p, int32_t layer, int32_t slice, const void* q
   a.part_acc = (float*)(ws + p->ws.part_acc);
   a.part_ml = (float*)(ws + p->ws.part_ml);
   a.seq_base = (const int32_t*)(ws + p->ws.seq_base);
-  a.order = (const int32_t*)(ws + p->ws.order);
+  a.chunk_blocks = p->chunk_tokens / p->cfg.block_tokens;
   a.done = (int32_t*)(ws + p->ws.done);
   a.out = (float*)out;
   a.err = (uint32_t*)(ws + p->ws.header);
@@ -601,9 +601,9 @@ int kv_attn_bind(vkv_pool* p, void* workspace, uint64_t workspace_bytes, void* s
   if (st != VKV_OK) return st;
   char* h = (char*)p->stage;
   std::memset(h, 0, p->ws.upload_bytes);   // flag word and per-(sequence, kv head) counters start at zero
-  std::memcpy(h + p->ws.work, p->work.data(), p->work.size() * sizeof(WorkItem));
+  WorkItem* hw = (WorkItem*)(h + p->ws.work);
+  for (size_t i = 0; i < p->order.size(); ++i) hw[i] = p->work[p->order[i]];   // the device copy is in launch order
   std::memcpy(h + p->ws.seq_base, p->seq_base.data(), p->seq_base.size() * 4);
-  std::memcpy(h + p->ws.order, p->order.data(), p->order.size() * 4);
   VKV_HIP(hipMemcpyAsync(workspace, h, p->ws.upload_bytes, hipMemcpyHostToDevice, (hipStream_t)stream));
   VKV_HIP(hipEventRecord(p->stage_ev, (hipStream_t)stream));
   p->stage_inflight = true;

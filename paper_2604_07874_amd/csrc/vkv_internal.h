@@ -38,14 +38,13 @@ struct WorkItem {   // matches int4 on the device
 // Byte offsets of the pieces of the attention workspace.
 struct WorkspaceLayout {
   uint64_t header = 0;       // 256 bytes; word 0 = bad-table-entry flag
-  uint64_t work = 0;         // WorkItem[n_items]
+  uint64_t work = 0;         // WorkItem[n_items], in launch order (a permutation inside each slice)
   uint64_t seq_base = 0;     // int32[num_seqs + 1]: first item of each sequence
-  uint64_t order = 0;        // int32[n_items]: launch order (a permutation inside each slice)
   uint64_t done = 0;         // int32[num_seqs][kv_heads]: chunks finished in the current layer
   uint64_t part_ml = 0;      // float[n_items][G][2]: running max (log2 units), sum of exponentials
   uint64_t part_acc = 0;     // float[n_items][G][D]: exp-weighted sum of V rows
   uint64_t total = 0;
-  uint64_t upload_bytes = 0; // header + work + seq_base + order + done are written by kv_attn_bind
+  uint64_t upload_bytes = 0; // header + work + seq_base + done are written by kv_attn_bind
 };
 
 inline uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
@@ -55,8 +54,7 @@ inline WorkspaceLayout workspace_layout(int64_t n_items, int64_t num_seqs, int H
   w.header = 0;
   w.work = 256;
   w.seq_base = w.work + (uint64_t)n_items * sizeof(WorkItem);
-  w.order = w.seq_base + (uint64_t)(num_seqs + 1) * 4;
-  w.done = w.order + (uint64_t)n_items * 4;
+  w.done = w.seq_base + (uint64_t)(num_seqs + 1) * 4;
   w.upload_bytes = w.done + (uint64_t)num_seqs * Hkv * 4;
   w.part_ml = align_up(w.upload_bytes, 256);
   w.part_acc = align_up(w.part_ml + (uint64_t)n_items * G * 2 * 4, 256);

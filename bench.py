@@ -242,6 +242,10 @@ def main():
     read_big_ms = timed_ms(lambda i: vkv.kv_probe_read(base_addr, big, sink, stream), 4)
     read_launch_ms = timed_ms(lambda i: vkv.kv_probe_read(base_addr + (i % n_regions) * launch_sized, launch_sized,
                                                           sink, stream), 16)
+    # the attention kernel's own reads without its arithmetic: slices of all layers in turn
+    n_probe = L * info.n_slices
+    probe_ms = timed_ms(lambda i: [vkv.kv_probe_attn_reads(pool, (i * 7 + l) % L, sl, tables, ws, sink, stream)
+                                   for l in range(L) for sl in range(info.n_slices)], 2) / n_probe
     cp_bytes = 1 << 30
     cp_a = torch.empty(cp_bytes, dtype=torch.uint8, device=dev)
     cp_b = torch.empty(cp_bytes, dtype=torch.uint8, device=dev)
@@ -251,11 +255,13 @@ def main():
         "sequential_read_GBps": round(big / read_big_ms / 1e6, 1), "sequential_read_bytes": int(big),
         "sequential_read_at_launch_size_GBps": round(launch_sized / read_launch_ms / 1e6, 1),
         "launch_size_bytes": int(launch_sized),
+        "attention_reads_only_GBps": round(decode_bytes_layer / info.n_slices / probe_ms / 1e6, 1),
         "runtime_copy_traffic_GBps": round(2 * cp_bytes / copy_ms / 1e6, 1), "copy_bytes": cp_bytes,
     }
     if roofline is not None:
         roofline["frac_of_read_ceiling_at_launch_size"] = round(
             roofline["achieved"] / ceilings["sequential_read_at_launch_size_GBps"], 4)
+        roofline["frac_of_own_reads_only"] = round(roofline["achieved"] / ceilings["attention_reads_only_GBps"], 4)
     if roofline_reclaim is not None:
         roofline_reclaim["frac_of_runtime_copy"] = round(
             roofline_reclaim["achieved"] / ceilings["runtime_copy_traffic_GBps"], 4)

@@ -434,6 +434,15 @@ int kv_profile_read(vkv_pool* pool, vkv_profile_record* out_host, int32_t cap, i
  * Errors: VKV_E_INVAL, VKV_E_HIP. */
 int kv_probe_read(const void* src_dev, uint64_t bytes, void* sink_dev, void* stream);
 
+/* Launches, for one slice of the bound plan, a kernel that performs the memory
+ * reads of paged_decode_attn_slice (same work items, same 4 KiB runs of K and V,
+ * same number of requests in flight) and none of its arithmetic: the rate this
+ * reaches is what the access pattern allows.  Arguments as for
+ * paged_decode_attn_slice; sink_dev: 256 bytes of device scratch, 16-byte aligned.
+ * Errors: as paged_decode_attn_slice. */
+int kv_probe_attn_reads(vkv_pool* pool, int32_t layer, int32_t slice, const int32_t* block_table,
+                        int32_t max_blk, void* workspace, void* sink_dev, void* stream);
+
 /* Enqueues the runtime's own device-to-device copy of bytes bytes (regions must
  * not overlap).  Errors: VKV_E_INVAL, VKV_E_HIP. */
 int kv_probe_copy(void* dst_dev, const void* src_dev, uint64_t bytes, void* stream);

@@ -25,7 +25,7 @@ __all__ = [
     "kv_prefill_merge", "kv_prefill_run_layer", "kv_prefill_check", "VKV_PROF_PREFILL", "VKV_PROF_PREFILL_MERGE",
     "kv_select_handles", "kv_invalidate_handles", "MiadConfig", "MiadStep", "kv_miad_init", "kv_miad_destroy",
     "kv_miad_observe", "kv_gate_init", "kv_gate_destroy", "kv_gate_online_busy", "kv_gate_online_idle",
-    "kv_gate_poll", "kv_gate_stats", "kv_probe_read", "kv_probe_copy", "kv_sched_set_overlap",
+    "kv_gate_poll", "kv_gate_stats", "kv_probe_read", "kv_probe_copy", "kv_probe_attn_reads", "kv_sched_set_overlap",
 ]
 
 VKV_OK, VKV_YIELDED = 0, 1
@@ -143,6 +143,7 @@ _sigs = {
     "kv_profile_read": (C.c_int, [_P, _P, C.c_int32, _I32P]),
     "kv_sched_set_overlap": (C.c_int, [_P, C.c_int32]),
     "kv_probe_read": (C.c_int, [_P, C.c_uint64, _P, _P]),
+    "kv_probe_attn_reads": (C.c_int, [_P, C.c_int32, C.c_int32, _P, C.c_int32, _P, _P, _P]),
     "kv_probe_copy": (C.c_int, [_P, _P, C.c_uint64, _P]),
 }
 for _name, (_res, _args) in _sigs.items():
@@ -333,6 +334,11 @@ def kv_sched_set_overlap(pool, enable: bool):
 # ---- bandwidth yardsticks ---------------------------------------------------------
 def kv_probe_read(src_dev, nbytes: int, sink_dev, stream=None):
     _check(lib.kv_probe_read(_dev(src_dev), nbytes, _dev(sink_dev), _stream(stream)))
+
+
+def kv_probe_attn_reads(pool, layer: int, slice_idx: int, block_table, workspace, sink_dev, stream=None):
+    _check(lib.kv_probe_attn_reads(pool, layer, slice_idx, _dev(block_table), block_table.shape[-1], _dev(workspace),
+                                   _dev(sink_dev), _stream(stream)))
 
 
 def kv_probe_copy(dst_dev, src_dev, nbytes: int, stream=None):

@@ -147,9 +147,9 @@ __global__ __launch_bounds__(256, 2) void paged_decode_attn_slice_kernel(const A
         const ldvec* ks = reinterpret_cast<const ldvec*>(kplane + (size_t)blk * p.block_elems);
         const ldvec* vs = reinterpret_cast<const ldvec*>(kplane + (size_t)blk * p.block_elems + p.v_off);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) kr[b * 4 + r] = ks[r * 64 + lane];
+        for (int r = 0; r < 4; ++r) kr[b * 4 + r] = __builtin_nontemporal_load(ks + r * 64 + lane);   // read once
 #pragma unroll
-        for (int r = 0; r < 4; ++r) vr[b * 4 + r] = vs[r * 64 + lane];
+        for (int r = 0; r < 4; ++r) vr[b * 4 + r] = __builtin_nontemporal_load(vs + r * 64 + lane);
       }
     }
   };
@@ -345,6 +345,55 @@ __global__ __launch_bounds__(256, 2) void paged_decode_attn_slice_kernel(const A
 }
 
 // ---- host ---------------------------------------------------------------------------
+
+// Yardstick: the memory accesses of the slice kernel without its arithmetic.  Same work items,
+// same 4 KiB runs, same 16 loads per wave and group requested one group ahead; the values are
+// xor-ed and stored only if they equal one fixed pattern.  What this reads per second is what the
+// access pattern allows; the gap to the real kernel is compute, merge and bookkeeping.
+template <int D>
+__global__ __launch_bounds__(256, 2) void paged_read_probe_kernel(const AttnParams p, u32x4* __restrict__ sink) {
+  using ldvec = typename LdVec<D>::type;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const WorkItem it = p.work[p.item_first + blockIdx.x];
+  const int ntok = it.n_tokens;
+  const int ngroups = (ntok + kGroupTokens - 1) / kGroupTokens;
+  const int32_t* trow = p.table + (size_t)it.seq * p.max_blk + it.first_block;
+  const uint16_t* kplane = p.pool + (size_t)it.kv_head * (16 * D);
+  const int nblk_item = (ntok + 15) >> 4;
+  const int32_t tb0 = lane < nblk_item ? trow[lane] : -1;
+  const int32_t tb1 = 64 + lane < nblk_item ? trow[64 + lane] : -1;
+  ldvec r[16];
+  auto issue = [&](int grp) {
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      const int bi = grp * 2 + b;
+      const int32_t blk = bi < 64 ? __builtin_amdgcn_readlane(tb0, bi & 63) : __builtin_amdgcn_readlane(tb1, bi & 63);
+      if (blk < 0 || blk >= p.NB) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) r[b * 8 + i] = ldvec{};
+      } else {
+        const ldvec* ks = reinterpret_cast<const ldvec*>(kplane + (size_t)blk * p.block_elems);
+        const ldvec* vs = reinterpret_cast<const ldvec*>(kplane + (size_t)blk * p.block_elems + p.v_off);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r[b * 8 + i] = __builtin_nontemporal_load(ks + i * 64 + lane);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r[b * 8 + 4 + i] = __builtin_nontemporal_load(vs + i * 64 + lane);
+      }
+    }
+  };
+  ldvec acc{};
+  int grp = wave;
+  if (grp < ngroups) issue(grp);
+  for (; grp < ngroups; grp += 4) {
+    ldvec x{};
+#pragma unroll
+    for (int i = 0; i < 16; ++i) x ^= r[i];
+    if (grp + 4 < ngroups) issue(grp + 4);
+    acc ^= x;
+  }
+  if (acc[0] == 0x9E3779B9u && acc[1] == 0x7F4A7C15u) sink[threadIdx.x & 15] = u32x4{acc[0], acc[1], 0u, 0u};
+}
 
 static int check_bound(vkv_pool* p, const void* workspace, const char* who) {
   if (!p) { set_error("%s: null pool", who); return VKV_E_INVAL; }
@@ -621,6 +670,34 @@ int paged_decode_attn_slice(vkv_pool* p, int32_t layer, int32_t slice, const voi
     return VKV_E_INVAL;
   }
   return launch_slice(p, layer, slice, q, table, max_blk, workspace, out, scale, (hipStream_t)stream);
+}
+
+int kv_probe_attn_reads(vkv_pool* p, int32_t layer, int32_t slice, const int32_t* table, int32_t max_blk,
+                        void* workspace, void* sink, void* stream) {
+  int st = check_slice_args(p, layer, workspace, table, max_blk, workspace, workspace, "kv_probe_attn_reads");
+  if (st != VKV_OK) return st;
+  if (!sink || (uintptr_t)sink % 16) { set_error("kv_probe_attn_reads: sink must be a 16-byte aligned device pointer"); return VKV_E_INVAL; }
+  if (slice < 0 || slice >= (int32_t)p->slice_start.size() - 1) {
+    set_error("kv_probe_attn_reads: slice %d out of range [0,%d)", slice, (int)p->slice_start.size() - 1);
+    return VKV_E_INVAL;
+  }
+  const int32_t first = p->slice_start[slice], count = p->slice_start[slice + 1] - first;
+  const int D = p->cfg.head_dim;
+  AttnParams a{};
+  a.pool = (const uint16_t*)p->cfg.base + (uint64_t)layer * ((uint64_t)2 * p->cfg.num_kv_heads * 16 * D);
+  a.work = (const WorkItem*)((char*)workspace + p->ws.work);
+  a.table = table;
+  a.block_elems = p->block_elems;
+  a.v_off = (uint32_t)(p->cfg.num_kv_heads * 16 * D);
+  a.item_first = first;
+  a.max_blk = max_blk;
+  a.NB = p->cfg.num_blocks;
+  if (D == 128)
+    hipLaunchKernelGGL(paged_read_probe_kernel<128>, dim3((unsigned)count), dim3(256), 0, (hipStream_t)stream, a, (u32x4*)sink);
+  else
+    hipLaunchKernelGGL(paged_read_probe_kernel<64>, dim3((unsigned)count), dim3(256), 0, (hipStream_t)stream, a, (u32x4*)sink);
+  VKV_HIP(hipGetLastError());
+  return VKV_OK;
 }
 
 int kv_attn_check(vkv_pool* p, void* workspace, void* stream) {

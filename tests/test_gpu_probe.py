@@ -22,3 +22,26 @@ def test_probe_read_and_copy():
         with pytest.raises(vkv.VkvError) as ei:
             vkv.kv_probe_read(src, bad, sink)
         assert ei.value.code == vkv.VKV_E_INVAL
+
+
+def test_probe_attention_reads_runs_over_a_bound_plan():
+    import numpy as np
+    import torch
+    import synth
+    from gpu_util import DeviceCase
+    c = DeviceCase(synth.workload("llama8b_small"), 3)
+    try:
+        vkv = c.vkv
+        info = c.plan(slice_bytes=1 << 20)
+        before = c.pool_t.clone()
+        sink = torch.zeros(256, dtype=torch.uint8, device="cuda:0")
+        for layer in range(c.wl.geom.num_layers):
+            for s in range(info.n_slices):
+                vkv.kv_probe_attn_reads(c.pool, layer, s, c.tables_t, c.ws, sink)
+        vkv.kv_attn_check(c.pool, c.ws)
+        assert torch.equal(c.pool_t, before) and int(sink.sum()) == 0
+        with pytest.raises(vkv.VkvError) as ei:
+            vkv.kv_probe_attn_reads(c.pool, 0, info.n_slices, c.tables_t, c.ws, sink)
+        assert ei.value.code == vkv.VKV_E_INVAL
+    finally:
+        c.close()

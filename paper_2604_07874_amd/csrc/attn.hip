@@ -353,10 +353,13 @@ __global__ __launch_bounds__(256, 2) void paged_decode_attn_slice_kernel(const A
 template <int D>
 __global__ __launch_bounds__(256, 2) void paged_read_probe_kernel(const AttnParams p, u32x4* __restrict__ sink) {
   using ldvec = typename LdVec<D>::type;
+  // as much LDS as keeps two workgroups on a compute unit, the slice kernel's own occupancy
+  __shared__ uint32_t occupancy_pad[(72 * 1024) / 4];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const WorkItem it = p.work[p.item_first + blockIdx.x];
   const int ntok = it.n_tokens;
+  if (ntok < 0) occupancy_pad[threadIdx.x] = (uint32_t)ntok;   // never true; keeps the array allocated
   const int ngroups = (ntok + kGroupTokens - 1) / kGroupTokens;
   const int32_t* trow = p.table + (size_t)it.seq * p.max_blk + it.first_block;
   const uint16_t* kplane = p.pool + (size_t)it.kv_head * (16 * D);

@@ -98,3 +98,62 @@ def test_full_size_attention_and_reclaim(full_case):
     out.fill_(float("nan"))
     run_layers(c, layers, out)
     assert np.array_equal(out.cpu().numpy(), first)
+
+
+def test_stress_size_overlapped_slices_and_reclaim():
+    """The largest configuration (200 GiB pool, byte offsets beyond 2^37, 34 slices per layer), with
+    the slices of a layer alternating between two streams: same bits as on one stream, sampled
+    outputs against the oracle, reclamation of the top 16 GiB against the integer oracle."""
+    from gpu_util import DeviceCase, oracle_attention_sampled
+    free, _ = torch.cuda.mem_get_info()
+    wl = synth.workload("stress")
+    if free < wl.geom.pool_bytes + (16 << 30):
+        pytest.skip("not enough free HBM for the 200 GiB pool")
+    print("filling the pool", flush=True)
+    c = DeviceCase(wl, seed=1, host_pool=False)
+    try:
+        g, vkv = wl.geom, c.vkv
+        info = c.plan()
+        assert info.n_slices > 8
+        print(f"items {info.n_items} slices {info.n_slices} kv bytes/layer {info.kv_bytes_per_layer}", flush=True)
+        layers = [0, g.num_layers - 1]
+        out = torch.full((g.num_layers, wl.num_seqs, g.num_q_heads, g.head_dim), float("nan"), dtype=torch.float32,
+                         device="cuda:0")
+        run_layers(c, layers, out)
+        one_stream = out[layers].cpu().numpy()
+        vkv.kv_sched_set_overlap(c.pool, True)
+        out.fill_(float("nan"))
+        run_layers(c, layers, out)
+        torch.cuda.synchronize()
+        assert np.array_equal(out[layers].cpu().numpy(), one_stream)
+        print("overlapped pass: identical bits", flush=True)
+        order = np.argsort(c.st.ctx_len)
+        seqs = [int(order[0]), int(order[-1])]
+        ref = oracle_attention_sampled(wl, c.seed, c.st.tables, c.st.ctx_len, layers[1], seqs)
+        for s_ in seqs:
+            err = float(np.max(np.abs(one_stream[1, s_].astype(np.float64) - ref[s_])))
+            print(f"layer {layers[1]} seq {s_} ctx {int(c.st.ctx_len[s_])}: max|err| {err:.3e}", flush=True)
+            assert err <= TOL
+        lo, hi = wl.reclaim_range
+        orc = R.ReclaimOracle(g.num_blocks, g.blocks_per_handle, c.st.live, c.st.tables, None)
+        stats = vkv.kv_reclaim_range(c.pool, lo, hi, c.tables_t, c.remap_t)
+        status, src, dst, remap = orc.reclaim(lo, hi)
+        assert status == R.OK and stats.blocks_moved == len(src) > 10000
+        print(f"moved {len(src)} blocks = {stats.bytes_moved / 2**30:.2f} GiB", flush=True)
+        live, ranges = vkv.kv_pool_state(c.pool, g.num_blocks)
+        assert np.array_equal(live, orc.live) and ranges == [(lo, hi)]
+        assert np.array_equal(c.remap_t.cpu().numpy(), remap)
+        assert np.array_equal(c.tables_t.cpu().numpy(), orc.tables)
+        blocks = c.pool_t.view(g.num_blocks, g.block_elems)
+        poisoned = {b for b, _ in c.st.poisoned}
+        picks = [i for i in np.linspace(0, len(src) - 1, 8).astype(int) if int(src[i]) not in poisoned]
+        for i in picks:
+            want = synth.pool_bits_for_blocks(g, c.seed, [int(src[i])])[0]
+            assert np.array_equal(blocks[int(dst[i])].cpu().numpy().view(np.uint16), want)
+        blocks[lo:hi] = synth.BF16_NAN_BITS
+        out.fill_(float("nan"))
+        run_layers(c, layers, out)
+        torch.cuda.synchronize()
+        assert np.array_equal(out[layers].cpu().numpy(), one_stream)
+    finally:
+        c.close()

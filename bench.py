@@ -73,7 +73,10 @@ def main():
     ap.add_argument("--prefill-leg", action="store_true",
                     help="extra leg: causal prefill of the newest --prefill-tokens tokens of every sequence")
     ap.add_argument("--prefill-tokens", type=int, default=2048)
-    ap.add_argument("--prefill-slice-bytes", type=int, default=1 << 30)
+    ap.add_argument("--prefill-slice-bytes", type=int, default=512 << 20)
+    ap.add_argument("--prefill-one-stream", action="store_true",
+                    help="prefill leg without overlapped slices (then per-launch durations are additive)")
+    ap.add_argument("--prefill-yield-injections", type=int, default=200)
     ap.add_argument("--prefill-chunk-tokens", type=int, default=4096)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-launch-events", action="store_true",
@@ -503,6 +506,8 @@ def main():
         # query values: the generator's bits at the start of the pool serve as well as any
         pq.view(-1).copy_(pool_t[:pq.numel()])
         pout = torch.empty((pinfo.total_q, g.num_q_heads, g.head_dim), dtype=torch.float32, device=dev)
+        p_overlap = not args.prefill_one_stream
+        vkv.kv_sched_set_overlap(pool, p_overlap)
         vkv.kv_profile_enable(pool, pinfo.n_slices * 3 + 16)
         n_layers_p = min(L, 2)
         for layer in range(n_layers_p):           # warm-up
@@ -518,18 +523,52 @@ def main():
         psl = rec[rec["kind"] == vkv.VKV_PROF_PREFILL]
         vkv.kv_profile_enable(pool, 0)
         # overlapped launches: per-launch durations are not additive, rate by the wall clock instead
-        kern_s = dt if args.overlap_slices else float(psl["ms"].sum()) * 1e-3 / n_layers_p
+        kern_s = dt if p_overlap else float(psl["ms"].sum()) * 1e-3 / n_layers_p
         extra.update({
             "prefill_rows": int(pinfo.total_q), "prefill_slices_per_layer": int(pinfo.n_slices),
-            "prefill_items_per_layer": int(pinfo.n_items),
+            "prefill_items_per_layer": int(pinfo.n_items), "prefill_overlapped_slices": p_overlap,
+            "prefill_slice_bytes": args.prefill_slice_bytes, "prefill_chunk_tokens": args.prefill_chunk_tokens,
             "prefill_TFLOPs_wall": round(pinfo.flops_per_layer / dt / 1e12, 1),
-            "prefill_TFLOPs_kernel": None if args.overlap_slices else round(pinfo.flops_per_layer / kern_s / 1e12, 1),
+            "prefill_TFLOPs_kernel": None if p_overlap else round(pinfo.flops_per_layer / kern_s / 1e12, 1),
             "prefill_frac_of_mfma_bf16_peak": round(pinfo.flops_per_layer / kern_s / 2.5e15, 4),
             "prefill_ms_per_layer": round(dt * 1e3, 3),
             "prefill_slice_us_p50": round(percentile(psl["ms"], 50) * 1e3, 1),
             "prefill_slice_us_p99": round(percentile(psl["ms"], 99) * 1e3, 1),
             "prefill_kv_GBps": round(pinfo.kv_bytes_per_layer / kern_s / 1e9, 1),
         })
+        # yield latency of a prefill: request at a random instant of a layer, until compute is off the GPU
+        if args.prefill_yield_injections > 0:
+            prng = np.random.default_rng(args.seed + 2)
+            plat, preq = [], [0.0]
+
+            def prequester(delay):
+                time.sleep(delay)
+                preq[0] = time.perf_counter()
+                vkv.kv_yield_request(pool)
+
+            layer, cur, t_begin = 0, 0, time.time()
+            for _ in range(args.prefill_yield_injections):
+                if time.time() - t_begin > 40.0:
+                    break
+                th = threading.Thread(target=prequester, args=(float(prng.uniform(0.0, dt)),))
+                th.start()
+                landed = None
+                while landed is None:
+                    s_, cur = vkv.kv_prefill_run_layer(pool, layer, cur, pq, tables, pws, pout,
+                                                       max_inflight=args.max_inflight, stream=stream)
+                    if s_ == vkv.VKV_YIELDED:
+                        landed = time.perf_counter()
+                    else:
+                        layer, cur = (layer + 1) % n_layers_p, 0
+                th.join()
+                plat.append((landed - preq[0]) * 1e6)
+                vkv.kv_yield_clear(pool)
+            torch.cuda.synchronize()
+            extra.update({"prefill_yield_latency_us_p50": round(percentile(plat, 50), 1),
+                          "prefill_yield_latency_us_p99": round(percentile(plat, 99), 1),
+                          "prefill_yield_latency_us_max": round(max(plat), 1), "prefill_yield_injections": len(plat)})
+        vkv.kv_prefill_check(pool, pws, stream)
+        vkv.kv_sched_set_overlap(pool, bool(args.overlap_slices))
         del pws, pq, pout
 
     progress("CPU oracle baseline")

@@ -268,7 +268,7 @@ typedef struct vkv_prefill_plan_info {
   int32_t  n_items, n_slices, n_tiles;
   int32_t  tile_positions;      /* query positions per tile = 128 / (G rounded up to a power of two) */
   int32_t  total_q;             /* sum of q_len: rows of q and out */
-  int32_t  reserved;
+  int32_t  n_merge_steps;       /* launches the merge of split tiles is cut into (>= 1) */
   uint64_t workspace_bytes;
   uint64_t kv_bytes_per_layer;  /* K+V bytes all items read (tokens are re-read once per query tile) */
   uint64_t max_slice_kv_bytes;
@@ -310,11 +310,16 @@ int paged_prefill_attn_slice(vkv_pool* pool, int32_t layer, int32_t slice,
                              const void* q_bf16, const int32_t* block_table, int32_t max_blk,
                              void* workspace, void* out_f32, float softmax_scale, void* stream);
 
-/* Enqueues the merge of split tiles (log-sum-exp, chunk order) into out; call
- * after every slice of the layer has been enqueued on the same stream. */
-int kv_prefill_merge(vkv_pool* pool, void* workspace, void* out_f32, void* stream);
+/* Enqueues step `step` (0 .. n_merge_steps-1) of the merge of split tiles
+ * (log-sum-exp, chunk order) into out; every slice of the layer must have been
+ * enqueued on the same stream before.  The merge is cut into steps of bounded
+ * size (partial results + outputs of at most slice_bytes / 2) so that it cannot
+ * delay a yield by more than a slice does.  Steps are independent and idempotent. */
+int kv_prefill_merge(vkv_pool* pool, int32_t step, void* workspace, void* out_f32, void* stream);
 
-/* Slice scheduler for prefill: as kv_attn_run_layer, followed by the merge. */
+/* Slice scheduler for prefill: as kv_attn_run_layer, with the merge steps
+ * following the slices: *cursor_slice runs over 0 .. n_slices + n_merge_steps
+ * (that value on VKV_OK); a yield may land before any slice or merge step. */
 int kv_prefill_run_layer(vkv_pool* pool, int32_t layer, int32_t* cursor_slice,
                          const void* q_bf16, const int32_t* block_table, int32_t max_blk,
                          void* workspace, void* out_f32, float softmax_scale,

@@ -69,7 +69,7 @@ class ProfileRecord(C.Structure):
 
 class PrefillPlanInfo(C.Structure):
     _fields_ = [("n_items", C.c_int32), ("n_slices", C.c_int32), ("n_tiles", C.c_int32),
-                ("tile_positions", C.c_int32), ("total_q", C.c_int32), ("reserved", C.c_int32),
+                ("tile_positions", C.c_int32), ("total_q", C.c_int32), ("n_merge_steps", C.c_int32),
                 ("workspace_bytes", C.c_uint64), ("kv_bytes_per_layer", C.c_uint64),
                 ("max_slice_kv_bytes", C.c_uint64), ("flops_per_layer", C.c_double)]
 
@@ -125,7 +125,7 @@ _sigs = {
     "kv_prefill_plan_read": (C.c_int, [_P, _P, _P, _P, _P]),
     "kv_prefill_bind": (C.c_int, [_P, _P, C.c_uint64, _P]),
     "paged_prefill_attn_slice": (C.c_int, [_P, C.c_int32, C.c_int32, _P, _P, C.c_int32, _P, _P, C.c_float, _P]),
-    "kv_prefill_merge": (C.c_int, [_P, _P, _P, _P]),
+    "kv_prefill_merge": (C.c_int, [_P, C.c_int32, _P, _P, _P]),
     "kv_prefill_run_layer": (C.c_int, [_P, C.c_int32, _I32P, _P, _P, C.c_int32, _P, _P, C.c_float, C.c_int32, _P]),
     "kv_prefill_check": (C.c_int, [_P, _P, _P]),
     "kv_select_handles": (C.c_int, [_P, _P, C.c_int32, C.c_int32, _P, C.c_int32, _P, _P, _I32P, C.POINTER(C.c_int64)]),
@@ -375,8 +375,8 @@ def paged_prefill_attn_slice(pool, layer: int, slice_idx: int, q, block_table, w
                                         _dev(workspace), _dev(out), softmax_scale, _stream(stream)))
 
 
-def kv_prefill_merge(pool, workspace, out, stream=None):
-    _check(lib.kv_prefill_merge(pool, _dev(workspace), _dev(out), _stream(stream)))
+def kv_prefill_merge(pool, step: int, workspace, out, stream=None):
+    _check(lib.kv_prefill_merge(pool, step, _dev(workspace), _dev(out), _stream(stream)))
 
 
 def kv_prefill_run_layer(pool, layer: int, cursor: int, q, block_table, workspace, out,

@@ -462,17 +462,18 @@ static int check_slice_args(vkv_pool* p, int32_t layer, const void* q, const int
   return VKV_OK;
 }
 
-// Slice scheduler shared by decode and prefill: issues slices *cursor .. n_slices-1 through
-// `launch`, then `tail` (if any), keeping at most max_inflight launches unfinished; the ring of
-// events persists across calls.  Stops at a slice boundary when the yield flag is set.
+// Slice scheduler shared by decode and prefill: issues steps *cursor .. n_slices + n_tail - 1
+// (slices through `launch`, then n_tail follow-up steps through `tail`, all on the caller's
+// stream), keeping at most max_inflight launches unfinished; the ring of events persists across
+// calls.  Stops at a step boundary when the yield flag is set.
 // With overlap on, odd slices go to a second stream the pool owns (forked from and joined back
 // into the caller's stream inside this call), so the workgroups of the next slice fill the
 // compute units the tail of the previous one leaves idle; slices of one layer are independent
 // (results are merged through per-item partials), so their order does not matter.
 int run_slices(vkv_pool* p, int32_t* cursor, int32_t n_slices, int32_t max_inflight, hipStream_t hs,
-               const char* who, const std::function<int(int32_t, hipStream_t)>& launch,
-               const std::function<int()>& tail) {
-  if (!cursor || *cursor < 0 || *cursor > n_slices || max_inflight < 1 || max_inflight > kMaxInflight) {
+               const char* who, const std::function<int(int32_t, hipStream_t)>& launch, int32_t n_tail,
+               const std::function<int(int32_t)>& tail) {
+  if (!cursor || *cursor < 0 || *cursor > n_slices + n_tail || max_inflight < 1 || max_inflight > kMaxInflight) {
     set_error("%s: bad cursor or max_inflight", who);
     return VKV_E_INVAL;
   }
@@ -535,12 +536,18 @@ int run_slices(vkv_pool* p, int32_t* cursor, int32_t n_slices, int32_t max_infli
     if (on != hs) aux_used = true;
   }
   if ((st = join()) != VKV_OK) return st;
-  if (tail && *cursor < n_slices + 1) {
+  for (int32_t t = std::max(*cursor, n_slices) - n_slices; t < n_tail; ++t) {
+    if (p->yield_flag.load(std::memory_order_acquire)) {
+      st = drain();
+      if (st != VKV_OK) return st;
+      *cursor = n_slices + t;
+      return VKV_YIELDED;
+    }
     if ((st = admit()) != VKV_OK) return st;
-    if ((st = tail()) != VKV_OK) return st;
+    if ((st = tail(t)) != VKV_OK) return st;
     if ((st = track(hs)) != VKV_OK) return st;
   }
-  *cursor = n_slices;
+  *cursor = n_slices + n_tail;
   return VKV_OK;
 }
 
@@ -724,7 +731,7 @@ int kv_attn_run_layer(vkv_pool* p, int32_t layer, int32_t* cursor, const void* q
                     [&](int32_t s, hipStream_t on) {
                       return launch_slice(p, layer, s, q, table, max_blk, workspace, out, scale, on);
                     },
-                    nullptr);
+                    0, nullptr);
 }
 
 int kv_sched_set_overlap(vkv_pool* p, int32_t enable) {

@@ -282,7 +282,7 @@ __global__ __launch_bounds__(256, 2) void paged_prefill_attn_slice_kernel(const 
 // Merge of the chunks of every (tile, kv head) that was split: log-sum-exp merge in chunk order.
 template <int D>
 __global__ __launch_bounds__(256) void prefill_merge_kernel(const PrefillParams p) {
-  const int tile = blockIdx.x / p.Hkv, head = blockIdx.x - tile * p.Hkv;
+  const int tile = p.item_first + blockIdx.x / p.Hkv, head = blockIdx.x % p.Hkv;   // item_first = first tile of the step
   const int base = p.tile_base[tile];
   const int nch = (p.tile_base[tile + 1] - base) / p.Hkv;
   if (nch == 1) return;
@@ -376,10 +376,12 @@ static int pf_launch_slice(vkv_pool* p, int32_t layer, int32_t slice, const void
   return VKV_OK;
 }
 
-static int pf_launch_merge(vkv_pool* p, void* workspace, void* out, hipStream_t st) {
+// merge step `step` covers tiles [merge_start[step], merge_start[step + 1])
+static int pf_launch_merge(vkv_pool* p, int32_t step, void* workspace, void* out, hipStream_t st) {
   PrefillParams a = pf_params(p, 0, workspace, nullptr, 0, workspace, out, 0.f);
-  const int32_t n_tiles = (int32_t)p->pf.tile_base.size() - 1;
-  ProfScope prof(p, VKV_PROF_PREFILL_MERGE, 0, st);
+  a.item_first = p->pf.merge_start[step];
+  const int32_t n_tiles = p->pf.merge_start[step + 1] - a.item_first;
+  ProfScope prof(p, VKV_PROF_PREFILL_MERGE, step, st);
   hipLaunchKernelGGL(prefill_merge_kernel<128>, dim3((unsigned)(n_tiles * p->cfg.num_kv_heads)), dim3(256), 0, st, a);
   VKV_HIP(hipGetLastError());
   return VKV_OK;
@@ -450,6 +452,23 @@ int kv_prefill_plan(vkv_pool* p, const int32_t* ctx, const int32_t* q_len, int32
   max_slice = std::max(max_slice, acc);
   pl.slice_start.push_back((int32_t)pl.work.size());
   const uint64_t n_items = pl.work.size(), n_tiles = pl.tile_base.size() - 1;
+  // The merge of split tiles is cut into steps as well, so that it cannot hold up a yield: a step
+  // is a run of tiles whose partial results and outputs amount to at most slice_bytes / 2.
+  {
+    const uint64_t tile_part = (uint64_t)kTileColumns * D * 4 * Hkv, bound = std::max<uint64_t>(slice_bytes / 2, tile_part);
+    uint64_t acc_b = 0;
+    pl.merge_start.push_back(0);
+    for (size_t t = 0; t + 1 < pl.tile_base.size(); ++t) {
+      const uint64_t nch = (uint64_t)(pl.tile_base[t + 1] - pl.tile_base[t]) / Hkv;
+      const uint64_t b = nch > 1 ? (nch + 1) * tile_part : 0;
+      if (acc_b + b > bound && acc_b > 0) {
+        pl.merge_start.push_back((int32_t)t);
+        acc_b = 0;
+      }
+      acc_b += b;
+    }
+    pl.merge_start.push_back((int32_t)pl.tile_base.size() - 1);
+  }
   pl.off_work = 256;
   pl.off_tiles = pl.off_work + n_items * sizeof(WorkItem);
   pl.off_tile_base = pl.off_tiles + n_tiles * 16;
@@ -474,7 +493,7 @@ int kv_prefill_plan(vkv_pool* p, const int32_t* ctx, const int32_t* q_len, int32
     info->n_tiles = (int32_t)n_tiles;
     info->tile_positions = QP;
     info->total_q = p->pf.total_q;
-    info->reserved = 0;
+    info->n_merge_steps = (int32_t)p->pf.merge_start.size() - 1;
     info->workspace_bytes = p->pf.total;
     info->kv_bytes_per_layer = total;
     info->max_slice_kv_bytes = max_slice;
@@ -529,11 +548,15 @@ int paged_prefill_attn_slice(vkv_pool* p, int32_t layer, int32_t slice, const vo
   return pf_launch_slice(p, layer, slice, q, table, max_blk, workspace, out, scale, (hipStream_t)stream);
 }
 
-int kv_prefill_merge(vkv_pool* p, void* workspace, void* out, void* stream) {
+int kv_prefill_merge(vkv_pool* p, int32_t step, void* workspace, void* out, void* stream) {
   int st = pf_check_bound(p, workspace, "kv_prefill_merge");
   if (st != VKV_OK) return st;
   if (!out) { set_error("kv_prefill_merge: null output"); return VKV_E_INVAL; }
-  return pf_launch_merge(p, workspace, out, (hipStream_t)stream);
+  if (step < 0 || step >= (int32_t)p->pf.merge_start.size() - 1) {
+    set_error("kv_prefill_merge: step %d out of range [0,%d)", step, (int)p->pf.merge_start.size() - 1);
+    return VKV_E_INVAL;
+  }
+  return pf_launch_merge(p, step, workspace, out, (hipStream_t)stream);
 }
 
 int kv_prefill_run_layer(vkv_pool* p, int32_t layer, int32_t* cursor, const void* q, const int32_t* table,
@@ -546,7 +569,8 @@ int kv_prefill_run_layer(vkv_pool* p, int32_t layer, int32_t* cursor, const void
                     [&](int32_t s, hipStream_t on) {
                       return pf_launch_slice(p, layer, s, q, table, max_blk, workspace, out, scale, on);
                     },
-                    [&]() { return pf_launch_merge(p, workspace, out, hs); });
+                    (int32_t)p->pf.merge_start.size() - 1,
+                    [&](int32_t step) { return pf_launch_merge(p, step, workspace, out, hs); });
 }
 
 int kv_prefill_check(vkv_pool* p, void* workspace, void* stream) {

@@ -102,6 +102,7 @@ struct vkv_pool {
     std::vector<int32_t> tiles;            // [n_tiles][4] = (sequence, first q row, first position, positions)
     std::vector<int32_t> tile_base;        // first item of each tile (+1 sentinel)
     std::vector<int32_t> order;            // launch order of the items (a permutation within each slice)
+    std::vector<int32_t> merge_start;      // first tile of each merge step (+1 sentinel)
     uint64_t off_work = 0, off_tiles = 0, off_tile_base = 0, off_order = 0, off_ml = 0, off_acc = 0, upload_bytes = 0, total = 0;
   } pf;
 
@@ -164,7 +165,8 @@ struct ProfScope {
 
 // Slice scheduler shared by decode and prefill (attn.hip).
 int run_slices(vkv_pool* p, int32_t* cursor, int32_t n_slices, int32_t max_inflight, hipStream_t hs, const char* who,
-               const std::function<int(int32_t, hipStream_t)>& launch, const std::function<int()>& tail);
+               const std::function<int(int32_t, hipStream_t)>& launch, int32_t n_tail,
+               const std::function<int(int32_t)>& tail);
 
 // Host-side relocation plan; see kv_reclaim_plan.
 int plan_relocation(const vkv_pool* p, int32_t lo, int32_t hi,

@@ -33,11 +33,12 @@ def run_prefill(c, q, q_len, layer, slice_bytes, chunk_tokens, through_scheduler
     out = torch.full((info.total_q, g.num_q_heads, g.head_dim), float("nan"), dtype=torch.float32, device="cuda:0")
     if through_scheduler:
         st, cur = vkv.kv_prefill_run_layer(c.pool, layer, 0, q_t, c.tables_t, ws, out)
-        assert (st, cur) == (vkv.VKV_OK, info.n_slices)
+        assert (st, cur) == (vkv.VKV_OK, info.n_slices + info.n_merge_steps)
     else:
         for s in range(info.n_slices):
             vkv.paged_prefill_attn_slice(c.pool, layer, s, q_t, c.tables_t, ws, out)
-        vkv.kv_prefill_merge(c.pool, ws, out)
+        for step in range(info.n_merge_steps):
+            vkv.kv_prefill_merge(c.pool, step, ws, out)
     vkv.kv_prefill_check(c.pool, ws)
     return info, out.cpu().numpy(), (ws, q_t)
 
@@ -89,10 +90,15 @@ def test_prefill_yield_resume_and_reclaim_keep_the_bits(overlap):
         info, full, (ws, q_t) = run_prefill(c, q, q_len, 1, 1 << 20, 512)
         assert info.n_slices >= 6
         out = torch.empty((info.total_q, g.num_q_heads, g.head_dim), dtype=torch.float32, device="cuda:0")
-        for k in (0, info.n_slices // 2, info.n_slices - 1):
+        n, m = info.n_slices, info.n_merge_steps
+        assert m >= 3                               # the merge is cut into steps too
+        # a yield pending before slice k (k < n) or before merge step k - n
+        for k in (0, n // 2, n - 1, n, n + m // 2, n + m - 1):
             out.fill_(float("nan"))
-            for s in range(k):
+            for s in range(min(k, n)):
                 vkv.paged_prefill_attn_slice(c.pool, 1, s, q_t, c.tables_t, ws, out)
+            for t in range(max(0, k - n)):
+                vkv.kv_prefill_merge(c.pool, t, ws, out)
             vkv.kv_yield_request(c.pool)
             st, cur = vkv.kv_prefill_run_layer(c.pool, 1, k, q_t, c.tables_t, ws, out)
             assert (st, cur) == (vkv.VKV_YIELDED, k)
@@ -104,7 +110,7 @@ def test_prefill_yield_resume_and_reclaim_keep_the_bits(overlap):
                 assert stats.blocks_moved > 0
                 c.pool_t.view(g.num_blocks, g.block_elems)[lo:hi] = synth.BF16_NAN_BITS
             st, cur = vkv.kv_prefill_run_layer(c.pool, 1, cur, q_t, c.tables_t, ws, out)
-            assert (st, cur) == (vkv.VKV_OK, info.n_slices)
+            assert (st, cur) == (vkv.VKV_OK, info.n_slices + info.n_merge_steps)
             torch.cuda.synchronize()
             assert np.array_equal(out.cpu().numpy(), full), f"resume at slice {k}"
     finally:

@@ -96,3 +96,71 @@ def test_overlapped_slices_keep_stream_order_and_bits():
         vkv.kv_attn_check(c.pool, c.ws, side)
     finally:
         c.close()
+
+
+def test_hand_derived_exact_cases_through_the_library():
+    """The exact-rational cases of tests/golden/attention_exact_cases.json, embedded in head_dim 128
+    (extra dimensions zero), through the decode and the prefill kernels: checks the library against
+    hand-derived values, not against the oracle."""
+    import json
+    import math
+    import os
+    from fractions import Fraction
+    import paper_2604_07874_amd as vkv
+    from oracle.attention import PoolLayout
+    fix = json.load(open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "attention_exact_cases.json")))
+    gg = fix["geometry"]
+    D, d0 = 128, gg["head_dim"]
+    lay = PoolLayout(1, gg["num_kv_heads"], D, 16)
+    nb = 4                                            # one handle of 4 blocks; block 3 stays free
+
+    def bf16(x):
+        u = np.asarray(x, dtype=np.float32).view(np.uint32)
+        return ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+
+    pool = np.full(nb * lay.block_elems, synth.BF16_NAN_BITS, dtype=np.uint16)
+    for blk, kv, head, slot, vals in fix["pool_entries"]:
+        o = lay.vec_offset(blk, 0, kv, head, slot)
+        pool[o:o + D] = 0
+        pool[o:o + d0] = bf16(vals)
+    pool_t = torch.from_numpy(pool.view(np.int16)).cuda()
+    tables = np.array(fix["tables"], dtype=np.int32)
+    tables_t = torch.from_numpy(tables).cuda()
+    ctx = np.array(fix["ctx_len"], dtype=np.int32)
+    p = vkv.kv_pool_init(1, gg["num_q_heads"], gg["num_kv_heads"], D, nb, 4, base=pool_t)
+    vkv.kv_pool_adopt(p, np.array([0, 1, 2], dtype=np.int32))
+    scales = {"ln2": math.log(2.0), "ln3": math.log(3.0)}
+    try:
+        info = vkv.kv_attn_plan(p, ctx, 1 << 20, 32)
+        ws = torch.empty(info.workspace_bytes, dtype=torch.uint8, device="cuda:0")
+        vkv.kv_attn_bind(p, ws)
+        for case in fix["decode"]:
+            q = np.zeros((2, gg["num_q_heads"], D), dtype=np.float32)
+            q[:, :, :d0] = np.array(case["q"], dtype=np.float32)
+            q_t = torch.from_numpy(bf16(q).view(np.int16)).cuda()
+            out = torch.full((2, gg["num_q_heads"], D), float("nan"), dtype=torch.float32, device="cuda:0")
+            st, cur = vkv.kv_attn_run_layer(p, 0, 0, q_t, tables_t, ws, out, softmax_scale=scales[case["scale"]])
+            assert st == vkv.VKV_OK
+            vkv.kv_attn_check(p, ws)
+            got = out.cpu().numpy()
+            want = np.array([[[float(Fraction(x)) for x in head] for head in seq] for seq in case["expect"]])
+            assert np.max(np.abs(got[:, :, :d0] - want)) <= TOL * max(1.0, np.abs(want).max()), case["name"]
+            assert np.all(got[:, :, d0:] == 0.0)
+        for case in fix["prefill"]:
+            q_len = np.array([case["q_len"][0], 1], dtype=np.int32)      # the library wants q_len >= 1 everywhere
+            q = np.zeros((int(q_len.sum()), gg["num_q_heads"], D), dtype=np.float32)
+            q[:q_len[0], :, :d0] = np.array(case["q_seq0"], dtype=np.float32)
+            q_t = torch.from_numpy(bf16(q).view(np.int16)).cuda()
+            pinfo = vkv.kv_prefill_plan(p, ctx, q_len, 1 << 20, 32)
+            pws = torch.empty(pinfo.workspace_bytes, dtype=torch.uint8, device="cuda:0")
+            vkv.kv_prefill_bind(p, pws)
+            out = torch.full((pinfo.total_q, gg["num_q_heads"], D), float("nan"), dtype=torch.float32, device="cuda:0")
+            st, cur = vkv.kv_prefill_run_layer(p, 0, 0, q_t, tables_t, pws, out, softmax_scale=scales[case["scale"]])
+            assert st == vkv.VKV_OK
+            vkv.kv_prefill_check(p, pws)
+            got = out.cpu().numpy()
+            want = np.array([[float(Fraction(x)) for x in row] for row in case["expect_seq0"]])
+            for head in range(gg["num_q_heads"]):
+                assert np.max(np.abs(got[:q_len[0], head, :d0] - want)) <= TOL * max(1.0, np.abs(want).max()), case["name"]
+    finally:
+        vkv.kv_pool_destroy(p)

@@ -35,7 +35,7 @@ def measured_traffic_ratio(workload: str):
     or None when there is none for this workload or the kernel source has changed since."""
     import hashlib
     path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
-    src = os.path.join(ROOT, "paper_2604_07874_amd", "csrc", "attn.hip")
+    src = os.path.join(ROOT, "paper_2604_07874_amd", "csrc", "attn_kernel.inc")
     if not (os.path.exists(path) and os.path.exists(src)):
         return None
     kv = dict(l.split(":", 1) for l in open(path) if l.startswith("attn_"))
@@ -79,6 +79,10 @@ def main():
     ap.add_argument("--prefill-yield-injections", type=int, default=200)
     ap.add_argument("--prefill-chunk-tokens", type=int, default=4096)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-baseline-layers", type=int, default=6,
+                    help="layers of the whole batch the oracle is timed on (about 2 s of one core each at the 8B shape)")
+    ap.add_argument("--cpu-workers", type=int, default=min(16, os.cpu_count() or 1),
+                    help="worker processes for the all-cores timing of the oracle (0 = skip it)")
     ap.add_argument("--no-launch-events", action="store_true",
                     help="do not bracket launches with timing events (roofline fields become null)")
     args = ap.parse_args()
@@ -86,6 +90,14 @@ def main():
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
               file=sys.stderr)
         sys.exit(2)
+
+    # The oracle's worker processes are started before anything touches the GPU: they are plain CPU
+    # interpreters and must not be children forked from a process that has initialised it.
+    workers = None
+    if not args.no_cpu_baseline and args.cpu_workers > 1:
+        import multiprocessing as mp
+        workers = mp.get_context("spawn").Pool(args.cpu_workers, initializer=_oracle_worker_init)
+        workers.map(_oracle_worker_ready, range(args.cpu_workers))
 
     import torch
     import synth
@@ -508,7 +520,7 @@ def main():
         pout = torch.empty((pinfo.total_q, g.num_q_heads, g.head_dim), dtype=torch.float32, device=dev)
         p_overlap = not args.prefill_one_stream
         vkv.kv_sched_set_overlap(pool, p_overlap)
-        vkv.kv_profile_enable(pool, pinfo.n_slices * 3 + 16)
+        vkv.kv_profile_enable(pool, (pinfo.n_slices + pinfo.n_merge_steps) * 3 + 16)
         n_layers_p = min(L, 2)
         for layer in range(n_layers_p):           # warm-up
             vkv.kv_prefill_run_layer(pool, layer, 0, pq, tables, pws, pout, max_inflight=args.max_inflight, stream=stream)
@@ -521,12 +533,14 @@ def main():
         dt = (time.perf_counter() - t0) / n_layers_p
         rec = vkv.kv_profile_read(pool, 1 << 20)
         psl = rec[rec["kind"] == vkv.VKV_PROF_PREFILL]
+        pmg = rec[rec["kind"] == vkv.VKV_PROF_PREFILL_MERGE]
         vkv.kv_profile_enable(pool, 0)
         # overlapped launches: per-launch durations are not additive, rate by the wall clock instead
         kern_s = dt if p_overlap else float(psl["ms"].sum()) * 1e-3 / n_layers_p
         extra.update({
             "prefill_rows": int(pinfo.total_q), "prefill_slices_per_layer": int(pinfo.n_slices),
-            "prefill_items_per_layer": int(pinfo.n_items), "prefill_overlapped_slices": p_overlap,
+            "prefill_items_per_layer": int(pinfo.n_items), "prefill_merge_steps_per_layer": int(pinfo.n_merge_steps),
+            "prefill_overlapped_slices": p_overlap,
             "prefill_slice_bytes": args.prefill_slice_bytes, "prefill_chunk_tokens": args.prefill_chunk_tokens,
             "prefill_TFLOPs_wall": round(pinfo.flops_per_layer / dt / 1e12, 1),
             "prefill_TFLOPs_kernel": None if p_overlap else round(pinfo.flops_per_layer / kern_s / 1e12, 1),
@@ -535,6 +549,8 @@ def main():
             "prefill_slice_us_p50": round(percentile(psl["ms"], 50) * 1e3, 1),
             "prefill_slice_us_p99": round(percentile(psl["ms"], 99) * 1e3, 1),
             "prefill_kv_GBps": round(pinfo.kv_bytes_per_layer / kern_s / 1e9, 1),
+            "prefill_merge_us_per_layer": round(float(pmg["ms"].sum()) * 1e3 / n_layers_p, 1),
+            "prefill_merge_step_us_max": round(float(pmg["ms"].max()) * 1e3, 1) if len(pmg) else None,
         })
         # yield latency of a prefill: request at a random instant of a layer, until compute is off the GPU
         if args.prefill_yield_injections > 0:
@@ -575,7 +591,11 @@ def main():
     # ---- the CPU oracle on a bounded sample of the same workload --------------------
     cpu_baseline = None
     if not args.no_cpu_baseline:
-        cpu_baseline = cpu_oracle_baseline(wl, st, pool_t, q_all, decode_bytes, reclaim_traffic)
+        cpu_baseline = cpu_oracle_baseline(wl, st, pool_t, q_all, decode_bytes, reclaim_traffic,
+                                           args.cpu_baseline_layers, workers, args.cpu_workers, progress)
+    if workers is not None:
+        workers.close()
+        workers.join()
 
     vkv.kv_pool_destroy(pool)
     line = {
@@ -599,8 +619,36 @@ def main():
     print(json.dumps(line), flush=True)
 
 
-def cpu_oracle_baseline(wl, st, pool_t, q_all, decode_bytes, reclaim_traffic):
-    """Times the oracle (as it stands, one thread) on a sample and scales to one step's byte mix."""
+def _oracle_worker_init():
+    try:
+        from threadpoolctl import threadpool_limits
+        threadpool_limits(limits=1)
+    except Exception:   # pragma: no cover
+        pass
+
+
+def _oracle_worker_ready(i):
+    import oracle.attention   # noqa: F401  (pay the import before anything is timed)
+    return i
+
+
+def _oracle_worker_task(task):
+    """One (layer file, sequence) unit of the oracle's attention; returns nothing of interest."""
+    path, geom, seq = task
+    from oracle.attention import PoolLayout, paged_decode_attention
+    z = np.load(path, mmap_mode="r")
+    meta = np.load(path + ".meta.npz")
+    lay = PoolLayout(1, geom[0], geom[1], geom[2])
+    paged_decode_attention(z, lay, meta["q"], meta["tables"], meta["ctx"], 0, seqs=[seq])
+    return seq
+
+
+def cpu_oracle_baseline(wl, st, pool_t, q_all, decode_bytes, reclaim_traffic, n_layers, workers, n_workers, progress):
+    """Times the oracle as it stands on a sample (the whole batch, the first n_layers layers, plus a
+    reclamation of a 1024-block pool) with one thread, and again over worker processes, and scales
+    both to one step's byte mix."""
+    import contextlib
+    import tempfile
     import torch
     from oracle.attention import PoolLayout, paged_decode_attention
     from oracle.reclaim import ReclaimOracle
@@ -609,52 +657,85 @@ def cpu_oracle_baseline(wl, st, pool_t, q_all, decode_bytes, reclaim_traffic):
     except Exception:   # pragma: no cover
         threadpool_limits = None
     g = wl.geom
-    layer = 0
-    n_seq = min(wl.num_seqs, 16)
-    # compact one-layer pool holding only the sampled sequences' blocks (ids renumbered; the
-    # attention result does not depend on block ids)
+    n_layers = max(1, min(n_layers, g.num_layers))
+    n_seq = wl.num_seqs
+    # compact one-layer pools holding only the batch's blocks (ids renumbered; the attention result
+    # does not depend on block ids)
     rows = st.tables[:n_seq]
     ids = np.unique(rows[rows >= 0])
     renum = np.full(g.num_blocks, -1, dtype=np.int32)
     renum[ids] = np.arange(len(ids), dtype=np.int32)
     layer_elems = 2 * g.num_kv_heads * g.block_tokens * g.head_dim
-    blocks = pool_t.view(g.num_blocks, g.block_elems)[torch.from_numpy(ids).to(pool_t.device).long(),
-                                                       layer * layer_elems:(layer + 1) * layer_elems]
-    sample_pool = blocks.cpu().numpy().view(np.uint16).reshape(-1)
+    ids_t = torch.from_numpy(ids).to(pool_t.device).long()
     sample_tables = np.where(rows >= 0, renum[np.maximum(rows, 0)], -1).astype(np.int32)
     lay = PoolLayout(1, g.num_kv_heads, g.head_dim, g.block_tokens)
-    q = q_all[layer, :n_seq].cpu().numpy().view(np.uint16)
     ctx = st.ctx_len[:n_seq]
-    import contextlib
-    with (threadpool_limits(limits=1) if threadpool_limits else contextlib.nullcontext()):
-        t0 = time.perf_counter()
-        paged_decode_attention(sample_pool, lay, q, sample_tables, ctx, 0)
-        t_attn = time.perf_counter() - t0
-        attn_bytes = int(ctx.sum()) * g.kv_bytes_per_token_layer
-        # reclamation: the top 512 blocks of the pool as a pool of their own, upper quarter reclaimed
-        nb_s = min(512, g.num_blocks) // g.blocks_per_handle * g.blocks_per_handle
-        base = g.num_blocks - nb_s
-        rc = max(g.blocks_per_handle, nb_s // 4 // g.blocks_per_handle * g.blocks_per_handle)
-        live = st.live[base:].copy()
-        if (live[:nb_s - rc] == 0).sum() < live[nb_s - rc:].sum():
-            live[:nb_s - rc] = 0            # crowded sample: make room, the copy cost is what is timed
-        pool_s = pool_t.view(g.num_blocks, g.block_elems)[base:].cpu().numpy().view(np.uint16)
-        tabs = np.flatnonzero(live).astype(np.int32).reshape(1, -1)
-        orc = ReclaimOracle(nb_s, g.blocks_per_handle, live, tabs, pool_s)
-        t0 = time.perf_counter()
-        status, src, dst, _ = orc.reclaim(nb_s - rc, nb_s)
-        t_rec = time.perf_counter() - t0
-        assert status == 0
-        rec_bytes = 2 * len(src) * g.block_bytes
-    attn_rate = attn_bytes / t_attn
-    rec_rate = rec_bytes / t_rec if t_rec > 0 and rec_bytes else float("inf")
-    step_s = decode_bytes / attn_rate + (reclaim_traffic / rec_rate if rec_bytes else 0.0)
-    return {"value": round((decode_bytes + reclaim_traffic) / step_s / 1e9, 4), "unit": "GB/s", "cores": 1,
-            "kind": "oracle",
-            "sample": (f"attention: layer 0 of the first {n_seq} sequences ({attn_bytes / 1e6:.0f} MB of K+V, "
-                       f"{t_attn:.1f} s); reclamation: top {nb_s} blocks as a pool, {len(src)} blocks moved "
-                       f"({rec_bytes / 1e6:.0f} MB read+written, {t_rec:.2f} s); scaled to one step's byte mix"),
-            "attention_GBps": round(attn_rate / 1e9, 4), "reclaim_GBps": round(rec_rate / 1e9, 3)}
+    attn_bytes = int(ctx.sum()) * g.kv_bytes_per_token_layer * n_layers
+    tmpdir = tempfile.mkdtemp(prefix="vkv_bench_", dir="/dev/shm" if os.path.isdir("/dev/shm") else None)
+    files = []
+    t_attn = 0.0
+    try:
+        with (threadpool_limits(limits=1) if threadpool_limits else contextlib.nullcontext()):
+            for layer in range(n_layers):
+                blocks = pool_t.view(g.num_blocks, g.block_elems)[ids_t, layer * layer_elems:(layer + 1) * layer_elems]
+                sample_pool = blocks.cpu().numpy().view(np.uint16).reshape(-1)
+                q = q_all[layer, :n_seq].cpu().numpy().view(np.uint16)
+                if workers is not None:
+                    try:
+                        path = os.path.join(tmpdir, f"layer{layer}.npy")
+                        np.save(path, sample_pool)
+                        np.savez(path + ".meta.npz", q=q, tables=sample_tables, ctx=ctx)
+                        files.append(path)
+                    except OSError as e:     # no room for the sample files: skip the all-cores timing
+                        progress(f"  cannot stage the sample for the worker processes: {e}")
+                        workers = None
+                t0 = time.perf_counter()
+                paged_decode_attention(sample_pool, lay, q, sample_tables, ctx, 0)
+                t_attn += time.perf_counter() - t0
+                progress(f"  oracle, one thread: layer {layer} done ({t_attn:.1f} s so far)")
+                del sample_pool, blocks
+            # reclamation: the top 1024 blocks of the pool as a pool of their own, upper quarter reclaimed
+            nb_s = min(1024, g.num_blocks) // g.blocks_per_handle * g.blocks_per_handle
+            base = g.num_blocks - nb_s
+            rc = max(g.blocks_per_handle, nb_s // 4 // g.blocks_per_handle * g.blocks_per_handle)
+            live = st.live[base:].copy()
+            if (live[:nb_s - rc] == 0).sum() < live[nb_s - rc:].sum():
+                live[:nb_s - rc] = 0            # crowded sample: make room, the copy cost is what is timed
+            pool_s = pool_t.view(g.num_blocks, g.block_elems)[base:].cpu().numpy().view(np.uint16)
+            tabs = np.flatnonzero(live).astype(np.int32).reshape(1, -1)
+            orc = ReclaimOracle(nb_s, g.blocks_per_handle, live, tabs, pool_s)
+            t0 = time.perf_counter()
+            status, src, dst, _ = orc.reclaim(nb_s - rc, nb_s)
+            t_rec = time.perf_counter() - t0
+            assert status == 0
+            rec_bytes = 2 * len(src) * g.block_bytes
+            del pool_s
+        attn_rate = attn_bytes / t_attn
+        rec_rate = rec_bytes / t_rec if t_rec > 0 and rec_bytes else float("inf")
+        step_s = decode_bytes / attn_rate + (reclaim_traffic / rec_rate if rec_bytes else 0.0)
+        result = {"value": round((decode_bytes + reclaim_traffic) / step_s / 1e9, 4), "unit": "GB/s", "cores": 1,
+                  "kind": "oracle",
+                  "sample": (f"attention: layers 0..{n_layers - 1} of all {n_seq} sequences ({attn_bytes / 1e6:.0f} MB of "
+                             f"K+V, {t_attn:.1f} s); reclamation: top {nb_s} blocks as a pool, {len(src)} blocks moved "
+                             f"({rec_bytes / 1e6:.0f} MB read+written, {t_rec:.2f} s); scaled to one step's byte mix"),
+                  "attention_GBps": round(attn_rate / 1e9, 4), "reclaim_GBps": round(rec_rate / 1e9, 3)}
+        if workers is not None:
+            # the same attention sample over worker processes, one (layer, sequence) unit at a time,
+            # longest first; the reclamation oracle is one memory copy per block and stays as timed
+            geom = (g.num_kv_heads, g.head_dim, g.block_tokens)
+            tasks = [(f, geom, int(s_)) for f in files for s_ in np.argsort(-ctx)]
+            t0 = time.perf_counter()
+            workers.map(_oracle_worker_task, tasks, chunksize=1)
+            t_mp = time.perf_counter() - t0
+            mp_rate = attn_bytes / t_mp
+            mp_step = decode_bytes / mp_rate + (reclaim_traffic / rec_rate if rec_bytes else 0.0)
+            result["all_cores"] = {"value": round((decode_bytes + reclaim_traffic) / mp_step / 1e9, 4), "unit": "GB/s",
+                                   "cores": n_workers, "attention_GBps": round(mp_rate / 1e9, 4),
+                                   "attention_seconds": round(t_mp, 2), "host_cpu_count": os.cpu_count()}
+        return result
+    finally:
+        import shutil
+        shutil.rmtree(tmpdir, ignore_errors=True)
 
 
 if __name__ == "__main__":

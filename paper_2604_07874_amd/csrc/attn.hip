@@ -1,35 +1,6 @@
-// Preemptible decode attention over the paged bf16 KV pool.
-//
-// One layer's attention is cut into work items (sequence, kv head, chunk of tokens) and
-// the items into slices of bounded KV bytes; each slice is one launch, so a yield lands
-// at a slice boundary (the sub-millisecond bound of paper Section 2.3, Challenge 1 and
-// Section 4.1, met without a driver).  The kernel is HBM-bound: it reads every K and V
-// byte of its tokens once; the MFMA units do the GQA q.K and p.V tiles.
-//
-// Kernel shape (wave64, gfx950):
-//   workgroup = 4 waves = one work item; wave w takes the 32-token groups w, w+4, ...
-//   Per group a wave issues 16 coalesced 16-byte-per-lane loads (K and V rows of two
-//   blocks): lane (c = lane%16, kg = lane/16) gets bytes [16c,16c+16) of rows kg, 4+kg,
-//   8+kg, 12+kg of each block.
-//   K rows go through a per-wave LDS tile to reach the A-operand layout of
-//   v_mfma_f32_16x16x32_bf16 (row = token, 8 consecutive d per lane); the B operand is q,
-//   one query head per column, columns >= G zero.
-//   Scores come back with column = query head = lane%16 and rows kg*4..kg*4+3; tokens are
-//   assigned to rows so that row kg*4+r is the token the same lane group loaded as its
-//   r-th V row.  The V registers therefore feed the second MFMA (out^T = V^T . P^T)
-//   straight from the loads after an in-register 16-bit transpose, with no LDS traffic:
-//   lane c owns output dims {c*D/16 + dt}.
-//   Softmax statistics are per lane (= per query head): running max m (log2 units), sum l,
-//   and the accumulator is rescaled when m grows.  l is summed from the bf16-rounded
-//   weights that enter the MFMA, so the result is an exact convex combination of V rows.
-//   The block ids of the item sit in two VGPRs (one table entry per lane) and are read
-//   with v_readlane, so no load sits between two groups' K/V fetches.
-//   Merge: an item that covers its whole sequence writes the output directly.  Otherwise
-//   it writes (max, sum, weighted V sum) to the workspace and bumps a per-(sequence, kv
-//   head) counter; the workgroup that brings the counter to the chunk count merges all
-//   chunks in chunk order (so the bits do not depend on which one arrives last), writes
-//   the output and zeroes the counter.  The counters live in the workspace, so this
-//   works across slices and across a yield.
+// Host side of the preemptible decode attention: work plan, workspace binding, slice launches,
+// the slice scheduler with the yield test, and the reads-only probe launcher.  The kernels are
+// in attn_kernel.inc.
 #include "vkv_internal.h"
 
 #include <algorithm>
@@ -39,364 +10,7 @@
 
 namespace vkv {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
-
-struct AttnParams {
-  const uint16_t* pool;      // pool base + layer offset (elements)
-  const WorkItem* work;      // device; in launch order: inside a slice, items by falling token count
-  const uint16_t* q;         // [S][Hq][D]
-  const int32_t* table;      // [rows][max_blk]
-  float* part_acc;           // [n_items][G][D]
-  float* part_ml;            // [n_items][G][2]
-  const int32_t* seq_base;   // [S+1] first item of each sequence
-  int32_t* done;             // [S][Hkv] chunks finished in the current layer
-  float* out;                // [S][Hq][D]
-  uint32_t* err;             // workspace header word 0
-  uint64_t block_elems;
-  uint32_t v_off;            // elements from a block's K plane to its V plane (one layer)
-  int32_t item_first;
-  int32_t max_blk;
-  int32_t Hq, Hkv, G, NB;
-  int32_t chunk_blocks;      // blocks per full chunk (chunk_tokens / 16)
-  float scale_log2;          // softmax scale * log2(e)
-};
-
-template <int D> struct LdVec;
-template <> struct LdVec<128> { using type = u32x4; };
-template <> struct LdVec<64> { using type = u32x2; };
-
-// device-scope relaxed atomic accesses: coherent across the whole GPU without cache maintenance
-__device__ __forceinline__ void st_dev(float* p, float v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float ld_dev(const float* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-// word j of a lane-row register as 32 bits (two bf16)
-__device__ __forceinline__ uint32_t word_of(const u32x4& v, int j) { return v[j]; }
-__device__ __forceinline__ uint32_t word_of(const u32x2& v, int j) { return v[j]; }
-
-template <int D>
-__global__ __launch_bounds__(256, 2) void paged_decode_attn_slice_kernel(const AttnParams p) {
-  using ldvec = typename LdVec<D>::type;
-  constexpr int EPL = D / 16;          // bf16 per lane per row (8 or 4)
-  constexpr int KS = D / 32;           // MFMA k-steps of the score tile
-  constexpr int RS = D * 2 + 16;       // LDS row stride in bytes (padded against bank conflicts)
-  constexpr int TILE = 32 * RS;        // one wave's K tile
-  constexpr float NEG_INF = -INFINITY;
-
-  __shared__ __attribute__((aligned(16))) unsigned char lds[4 * TILE];
-  __shared__ float sm_m[4][16], sm_l[4][16];
-
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int c16 = lane & 15, kg = lane >> 4;
-
-  const WorkItem it = p.work[p.item_first + blockIdx.x];   // workgroups start in grid order: longest items first
-  const int ntok = it.n_tokens;
-  const int ngroups = (ntok + kGroupTokens - 1) / kGroupTokens;
-  const int G = p.G;
-
-  // B operand of the score MFMA: column = query head, k index kg*8+j <-> d = 32*ks + 8*kg + j
-  bf16x8 qb[KS];
-  {
-    const bool valid = c16 < G;
-    const uint16_t* qrow = p.q + ((size_t)it.seq * p.Hq + (size_t)it.kv_head * G + (valid ? c16 : 0)) * D;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      u32x4 v = {0u, 0u, 0u, 0u};
-      if (valid) v = *reinterpret_cast<const u32x4*>(qrow + ks * 32 + kg * 8);
-      qb[ks] = __builtin_bit_cast(bf16x8, v);
-    }
-  }
-
-  const int32_t* trow = p.table + (size_t)it.seq * p.max_blk + it.first_block;
-  const uint16_t* kplane = p.pool + (size_t)it.kv_head * (16 * D);
-  unsigned char* tile = lds + wave * TILE;
-
-  // block ids of this item: lane j holds entries j and 64+j (chunk_tokens <= 2048)
-  const int nblk_item = (ntok + 15) >> 4;
-  const int32_t tb0 = lane < nblk_item ? trow[lane] : -1;
-  const int32_t tb1 = 64 + lane < nblk_item ? trow[64 + lane] : -1;
-
-  f32x4 acc[EPL];
-#pragma unroll
-  for (int dt = 0; dt < EPL; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float m_run = NEG_INF, l_run = 0.f;
-
-  ldvec kr[8], vr[8];   // [block b of the group][row slot r]: row 4r+kg of block b
-
-  auto issue = [&](int grp) {
-#pragma unroll
-    for (int b = 0; b < 2; ++b) {
-      const int bi = grp * 2 + b;
-      const bool have = bi < nblk_item;
-      const int32_t blk = bi < 64 ? __builtin_amdgcn_readlane(tb0, bi & 63) : __builtin_amdgcn_readlane(tb1, bi & 63);
-      if (blk < 0 || blk >= p.NB) {
-        if (have && lane == 0) atomicOr(p.err, 1u);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          kr[b * 4 + r] = ldvec{};
-          vr[b * 4 + r] = ldvec{};
-        }
-      } else {
-        const ldvec* ks = reinterpret_cast<const ldvec*>(kplane + (size_t)blk * p.block_elems);
-        const ldvec* vs = reinterpret_cast<const ldvec*>(kplane + (size_t)blk * p.block_elems + p.v_off);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) kr[b * 4 + r] = __builtin_nontemporal_load(ks + r * 64 + lane);   // read once
-#pragma unroll
-        for (int r = 0; r < 4; ++r) vr[b * 4 + r] = __builtin_nontemporal_load(vs + r * 64 + lane);
-      }
-    }
-  };
-
-  int grp = wave;
-  if (grp < ngroups) issue(grp);
-
-  for (; grp < ngroups; grp += 4) {
-    const int tok0 = grp * kGroupTokens;
-    const bool tail = tok0 + kGroupTokens > ntok;
-
-    // K rows -> LDS tile, row index = 16b + 4r + kg, 16-byte column c16
-#pragma unroll
-    for (int b = 0; b < 2; ++b)
-#pragma unroll
-      for (int r = 0; r < 4; ++r)
-        *reinterpret_cast<ldvec*>(tile + (b * 16 + 4 * r + kg) * RS + c16 * (EPL * 2)) = kr[b * 4 + r];
-
-    // V rows past the end of the sequence may hold anything (NaN included): zero them
-    if (tail) {
-#pragma unroll
-      for (int b = 0; b < 2; ++b)
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-          if (tok0 + b * 16 + 4 * r + kg >= ntok) vr[b * 4 + r] = ldvec{};
-    }
-
-    // A operands of the second MFMA: va[dt] = element dt of each of the lane's 8 V rows
-    bf16x8 va[EPL];
-#pragma unroll
-    for (int dt = 0; dt < EPL; ++dt) {
-      u32x4 w;
-      const uint32_t sel = (dt & 1) ? 0x07060302u : 0x05040100u;   // high or low halves of (hi=src0, lo=src1)
-#pragma unroll
-      for (int pr = 0; pr < 4; ++pr)
-        w[pr] = __builtin_amdgcn_perm(word_of(vr[2 * pr + 1], dt >> 1), word_of(vr[2 * pr], dt >> 1), sel);
-      va[dt] = __builtin_bit_cast(bf16x8, w);
-    }
-
-    const int next = grp + 4;
-    if (next < ngroups) issue(next);
-
-    // LDS operations of one wave execute in order; keep the compiler from reordering them
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-
-    // scores: tile b, MFMA row i <-> token 4*(i%4) + i/4 of block b
-    f32x4 sc[2];
-    const int trow_lds = 4 * (c16 & 3) + (c16 >> 2);
-#pragma unroll
-    for (int b = 0; b < 2; ++b) {
-      sc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const u32x4 a = *reinterpret_cast<const u32x4*>(tile + (b * 16 + trow_lds) * RS + (ks * 4 + kg) * 16);
-        sc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), qb[ks], sc[b], 0, 0, 0);
-      }
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-
-    // this lane: query head c16, tokens tok0 + 16b + 4r + kg
-    float x[8];
-    float mx = NEG_INF;
-#pragma unroll
-    for (int b = 0; b < 2; ++b)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const bool ok = !tail || (tok0 + b * 16 + 4 * r + kg < ntok);
-        const float v = ok ? sc[b][r] * p.scale_log2 : NEG_INF;
-        x[b * 4 + r] = v;
-        mx = fmaxf(mx, v);
-      }
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx);           // finite: every group holds a valid token
-    const float alpha = __builtin_exp2f(m_run - m_new);
-    bf16x8 pb;
-    float psum = 0.f;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const __bf16 pj = (__bf16)__builtin_exp2f(x[j] - m_new);
-      pb[j] = pj;
-      psum += (float)pj;
-    }
-    l_run = l_run * alpha + psum;
-    m_run = m_new;
-#pragma unroll
-    for (int dt = 0; dt < EPL; ++dt) {
-      acc[dt] *= alpha;
-      acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pb, acc[dt], 0, 0, 0);
-    }
-  }
-
-  // ---- merge the four waves (each covered a disjoint subset of the item's tokens) ----
-  l_run += __shfl_xor(l_run, 16);
-  l_run += __shfl_xor(l_run, 32);
-  __syncthreads();   // all waves are done with their K tiles
-  float* macc = reinterpret_cast<float*>(lds);   // [4][G][D]
-  if (c16 < G) {
-#pragma unroll
-    for (int dt = 0; dt < EPL; ++dt)
-#pragma unroll
-      for (int r = 0; r < 4; ++r)
-        macc[((size_t)wave * G + c16) * D + (kg * 4 + r) * EPL + dt] = acc[dt][r];
-    if (kg == 0) {
-      sm_m[wave][c16] = m_run;
-      sm_l[wave][c16] = l_run;
-    }
-  }
-  __syncthreads();
-  const int base = p.seq_base[it.seq];
-  // item id in plan order (sequence, chunk, kv head): partial results are stored under it
-  const size_t item = (size_t)base + (size_t)(it.first_block / p.chunk_blocks) * p.Hkv + it.kv_head;
-  const int nch = (p.seq_base[it.seq + 1] - base) / p.Hkv;   // chunks of this sequence
-  float* orow = p.out + ((size_t)it.seq * p.Hq + (size_t)it.kv_head * G) * D;
-  for (int e = threadIdx.x; e < G * D; e += 256) {
-    const int g = e / D, d = e - g * D;
-    float M = sm_m[0][g];
-#pragma unroll
-    for (int w = 1; w < 4; ++w) M = fmaxf(M, sm_m[w][g]);
-    float num = 0.f, den = 0.f;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const float wt = __builtin_exp2f(sm_m[w][g] - M);   // 0 for a wave that had no group
-      num += wt * macc[((size_t)w * G + g) * D + d];
-      den += wt * sm_l[w][g];
-    }
-    if (nch == 1) {
-      orow[e] = num / den;
-    } else {
-      st_dev(&p.part_acc[(item * G + g) * D + d], num);
-      if (d == 0) {
-        st_dev(&p.part_ml[(item * G + g) * 2 + 0], M);
-        st_dev(&p.part_ml[(item * G + g) * 2 + 1], den);
-      }
-    }
-  }
-  if (nch == 1) return;
-
-  // Publish the partial result, then count this chunk as done.  The partial results and the
-  // counter are only ever touched with device-scope atomic accesses, which are performed at
-  // the device's coherence point (not in the per-XCD L2), so no cache write-back or
-  // invalidation is needed: each wave waits until its stores are acknowledged, the barrier
-  // collects the waves, then thread 0 bumps the counter.
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-  __syncthreads();
-  __shared__ int sm_last;
-  int32_t* done = p.done + (size_t)it.seq * p.Hkv + it.kv_head;
-  if (threadIdx.x == 0)
-    sm_last = __hip_atomic_fetch_add(done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == nch - 1;
-  __syncthreads();
-  if (!sm_last) return;
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-
-  // Last chunk of this (sequence, kv head): merge all chunks, in chunk order.
-  // Stage every chunk's (max, sum) in LDS first so the loads below are independent.
-  float* cm = reinterpret_cast<float*>(lds);       // [nch][G]
-  float* cl = cm + (size_t)nch * G;                 // [nch][G]
-  for (int i = threadIdx.x; i < nch * G; i += 256) {
-    const int c = i / G, g = i - c * G;
-    const size_t ig = ((size_t)base + (size_t)c * p.Hkv + it.kv_head) * G + g;
-    cm[i] = ld_dev(&p.part_ml[ig * 2]);
-    cl[i] = ld_dev(&p.part_ml[ig * 2 + 1]);
-  }
-  __syncthreads();
-  for (int e = threadIdx.x; e < G * D; e += 256) {
-    const int g = e / D, d = e - g * D;
-    float M = NEG_INF;
-    for (int c = 0; c < nch; ++c) M = fmaxf(M, cm[c * G + g]);
-    float num = 0.f, den = 0.f;
-    for (int c0 = 0; c0 < nch; c0 += 8) {
-      float a[8];
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const int c = c0 + j < nch ? c0 + j : nch - 1;
-        a[j] = ld_dev(&p.part_acc[(((size_t)base + (size_t)c * p.Hkv + it.kv_head) * G + g) * D + d]);
-      }
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        if (c0 + j < nch) {
-          const float wt = __builtin_exp2f(cm[(c0 + j) * G + g] - M);
-          num += wt * a[j];
-          den += wt * cl[(c0 + j) * G + g];
-        }
-      }
-    }
-    orow[e] = num / den;
-  }
-  if (threadIdx.x == 0) __hip_atomic_store(done, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next layer
-}
-
-// ---- host ---------------------------------------------------------------------------
-
-// Yardstick: the memory accesses of the slice kernel without its arithmetic.  Same work items,
-// same 4 KiB runs, same 16 loads per wave and group requested one group ahead; the values are
-// xor-ed and stored only if they equal one fixed pattern.  What this reads per second is what the
-// access pattern allows; the gap to the real kernel is compute, merge and bookkeeping.
-template <int D>
-__global__ __launch_bounds__(256, 2) void paged_read_probe_kernel(const AttnParams p, u32x4* __restrict__ sink) {
-  using ldvec = typename LdVec<D>::type;
-  // as much LDS as keeps two workgroups on a compute unit, the slice kernel's own occupancy
-  __shared__ uint32_t occupancy_pad[(72 * 1024) / 4];
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const WorkItem it = p.work[p.item_first + blockIdx.x];
-  const int ntok = it.n_tokens;
-  if (ntok < 0) occupancy_pad[threadIdx.x] = (uint32_t)ntok;   // never true; keeps the array allocated
-  const int ngroups = (ntok + kGroupTokens - 1) / kGroupTokens;
-  const int32_t* trow = p.table + (size_t)it.seq * p.max_blk + it.first_block;
-  const uint16_t* kplane = p.pool + (size_t)it.kv_head * (16 * D);
-  const int nblk_item = (ntok + 15) >> 4;
-  const int32_t tb0 = lane < nblk_item ? trow[lane] : -1;
-  const int32_t tb1 = 64 + lane < nblk_item ? trow[64 + lane] : -1;
-  ldvec r[16];
-  auto issue = [&](int grp) {
-#pragma unroll
-    for (int b = 0; b < 2; ++b) {
-      const int bi = grp * 2 + b;
-      const int32_t blk = bi < 64 ? __builtin_amdgcn_readlane(tb0, bi & 63) : __builtin_amdgcn_readlane(tb1, bi & 63);
-      if (blk < 0 || blk >= p.NB) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) r[b * 8 + i] = ldvec{};
-      } else {
-        const ldvec* ks = reinterpret_cast<const ldvec*>(kplane + (size_t)blk * p.block_elems);
-        const ldvec* vs = reinterpret_cast<const ldvec*>(kplane + (size_t)blk * p.block_elems + p.v_off);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) r[b * 8 + i] = __builtin_nontemporal_load(ks + i * 64 + lane);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) r[b * 8 + 4 + i] = __builtin_nontemporal_load(vs + i * 64 + lane);
-      }
-    }
-  };
-  ldvec acc{};
-  int grp = wave;
-  if (grp < ngroups) issue(grp);
-  for (; grp < ngroups; grp += 4) {
-    ldvec x{};
-#pragma unroll
-    for (int i = 0; i < 16; ++i) x ^= r[i];
-    if (grp + 4 < ngroups) issue(grp + 4);
-    acc ^= x;
-  }
-  if (acc[0] == 0x9E3779B9u && acc[1] == 0x7F4A7C15u) sink[threadIdx.x & 15] = u32x4{acc[0], acc[1], 0u, 0u};
-}
+#include "attn_kernel.inc"
 
 static int check_bound(vkv_pool* p, const void* workspace, const char* who) {
   if (!p) { set_error("%s: null pool", who); return VKV_E_INVAL; }

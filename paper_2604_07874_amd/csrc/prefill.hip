@@ -45,6 +45,7 @@ struct PrefillParams {
   const int32_t* tiles;       // [n_tiles][4] = (sequence, first q row, first position, positions)
   const int32_t* tile_base;   // [n_tiles + 1]
   const int32_t* order;       // [n_items] launch order: within a slice, items by falling token count
+  const int32_t* merge_tiles; // tiles that were split into several chunks
   const uint16_t* q;          // [total_q][Hq][D]
   const int32_t* table;
   float* part_acc;            // [n_items][128][D]
@@ -279,30 +280,73 @@ __global__ __launch_bounds__(256, 2) void paged_prefill_attn_slice_kernel(const 
   }
 }
 
-// Merge of the chunks of every (tile, kv head) that was split: log-sum-exp merge in chunk order.
+// Merge of the chunks of one split (tile, kv head): log-sum-exp merge in chunk order.
+// Pass 1, one thread per column: the maximum over the chunks, then the chunk weights
+// 2^(m_c - M) into LDS (32 chunks at a time) and their weighted sum of the partial sums.
+// Pass 2, one thread per (column, four output dims): the weighted partial accumulators, with
+// the loads of four chunks in flight at a time, since this kernel is nothing but memory latency.
 template <int D>
 __global__ __launch_bounds__(256) void prefill_merge_kernel(const PrefillParams p) {
-  const int tile = p.item_first + blockIdx.x / p.Hkv, head = blockIdx.x % p.Hkv;   // item_first = first tile of the step
+  constexpr int kBatch = 32;
+  __shared__ float sm_w[kBatch][kTileColumns];
+  __shared__ float sm_M[kTileColumns], sm_den[kTileColumns];
+  // item_first = first entry of the step in the list of split tiles
+  const int tile = p.merge_tiles[p.item_first + blockIdx.x / p.Hkv], head = blockIdx.x % p.Hkv;
   const int base = p.tile_base[tile];
   const int nch = (p.tile_base[tile + 1] - base) / p.Hkv;
-  if (nch == 1) return;
   const int row0 = p.tiles[4 * tile + 1], n_pos = p.tiles[4 * tile + 3];
   const int G = p.G, gp_mask = (1 << p.gp_shift) - 1;
-  for (int e = threadIdx.x; e < kTileColumns * D; e += 256) {
-    const int col = e / D, d = e - col * D;
+  auto item_col = [&](int c, int col) { return ((size_t)base + (size_t)c * p.Hkv + head) * kTileColumns + col; };
+  const int tid = threadIdx.x;
+  if (tid < kTileColumns) {
+    float M = -INFINITY;
+    for (int c = 0; c < nch; ++c) M = fmaxf(M, p.part_ml[item_col(c, tid) * 2]);
+    sm_M[tid] = M;
+    sm_den[tid] = 0.f;
+  }
+  constexpr int VPR = D / 4;                         // float4 per column
+  f32x4 num[kTileColumns * VPR / 256];
+#pragma unroll
+  for (int i = 0; i < kTileColumns * VPR / 256; ++i) num[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int c0 = 0; c0 < nch; c0 += kBatch) {
+    const int nb = min(kBatch, nch - c0);
+    __syncthreads();                                 // sm_M ready / previous batch's weights consumed
+    if (tid < kTileColumns) {
+      const float M = sm_M[tid];
+      float den = sm_den[tid];
+      for (int j = 0; j < nb; ++j) {
+        const size_t ic = item_col(c0 + j, tid);
+        const float wt = __builtin_exp2f(p.part_ml[ic * 2] - M);   // 0 for a chunk this column cannot see
+        sm_w[j][tid] = wt;
+        den += wt * p.part_ml[ic * 2 + 1];
+      }
+      sm_den[tid] = den;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kTileColumns * VPR / 256; ++i) {
+      const int e = i * 256 + tid, col = e / VPR, v = e - col * VPR;
+      int j = 0;
+      for (; j + 4 <= nb; j += 4) {
+        f32x4 x[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          x[u] = *reinterpret_cast<const f32x4*>(p.part_acc + item_col(c0 + j + u, col) * D + v * 4);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) num[i] += sm_w[j + u][col] * x[u];
+      }
+      for (; j < nb; ++j)
+        num[i] += sm_w[j][col] * *reinterpret_cast<const f32x4*>(p.part_acc + item_col(c0 + j, col) * D + v * 4);
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < kTileColumns * VPR / 256; ++i) {
+    const int e = i * 256 + tid, col = e / VPR, v = e - col * VPR;
     const int cpos = col >> p.gp_shift, cg = col & gp_mask;
     if (cg >= G || cpos >= n_pos) continue;
-    float M = -INFINITY;
-    for (int c = 0; c < nch; ++c)
-      M = fmaxf(M, p.part_ml[(((size_t)base + (size_t)c * p.Hkv + head) * kTileColumns + col) * 2]);
-    float num = 0.f, den = 0.f;
-    for (int c = 0; c < nch; ++c) {
-      const size_t ic = ((size_t)base + (size_t)c * p.Hkv + head) * kTileColumns + col;
-      const float wt = __builtin_exp2f(p.part_ml[ic * 2] - M);   // 0 for a chunk this column cannot see
-      num += wt * p.part_acc[ic * D + d];
-      den += wt * p.part_ml[ic * 2 + 1];
-    }
-    p.out[((size_t)(row0 + cpos) * p.Hq + (size_t)head * G + cg) * D + d] = num / den;
+    const float inv = 1.0f / sm_den[col];
+    *reinterpret_cast<f32x4*>(p.out + ((size_t)(row0 + cpos) * p.Hq + (size_t)head * G + cg) * D + v * 4) = num[i] * inv;
   }
 }
 
@@ -347,6 +391,7 @@ static PrefillParams pf_params(vkv_pool* p, int32_t layer, const void* q, const 
   a.tiles = (const int32_t*)(ws + p->pf.off_tiles);
   a.tile_base = (const int32_t*)(ws + p->pf.off_tile_base);
   a.order = (const int32_t*)(ws + p->pf.off_order);
+  a.merge_tiles = (const int32_t*)(ws + p->pf.off_merge_tiles);
   a.q = (const uint16_t*)q;
   a.table = table;
   a.part_acc = (float*)(ws + p->pf.off_acc);
@@ -381,6 +426,7 @@ static int pf_launch_merge(vkv_pool* p, int32_t step, void* workspace, void* out
   PrefillParams a = pf_params(p, 0, workspace, nullptr, 0, workspace, out, 0.f);
   a.item_first = p->pf.merge_start[step];
   const int32_t n_tiles = p->pf.merge_start[step + 1] - a.item_first;
+  if (n_tiles == 0) return VKV_OK;   // no tile of this plan was split
   ProfScope prof(p, VKV_PROF_PREFILL_MERGE, step, st);
   hipLaunchKernelGGL(prefill_merge_kernel<128>, dim3((unsigned)(n_tiles * p->cfg.num_kv_heads)), dim3(256), 0, st, a);
   VKV_HIP(hipGetLastError());
@@ -453,27 +499,30 @@ int kv_prefill_plan(vkv_pool* p, const int32_t* ctx, const int32_t* q_len, int32
   pl.slice_start.push_back((int32_t)pl.work.size());
   const uint64_t n_items = pl.work.size(), n_tiles = pl.tile_base.size() - 1;
   // The merge of split tiles is cut into steps as well, so that it cannot hold up a yield: a step
-  // is a run of tiles whose partial results and outputs amount to at most slice_bytes / 2.
+  // is a run of split tiles whose partial results and outputs amount to at most slice_bytes / 2.
   {
     const uint64_t tile_part = (uint64_t)kTileColumns * D * 4 * Hkv, bound = std::max<uint64_t>(slice_bytes / 2, tile_part);
     uint64_t acc_b = 0;
     pl.merge_start.push_back(0);
     for (size_t t = 0; t + 1 < pl.tile_base.size(); ++t) {
       const uint64_t nch = (uint64_t)(pl.tile_base[t + 1] - pl.tile_base[t]) / Hkv;
-      const uint64_t b = nch > 1 ? (nch + 1) * tile_part : 0;
+      if (nch <= 1) continue;
+      const uint64_t b = (nch + 1) * tile_part;
       if (acc_b + b > bound && acc_b > 0) {
-        pl.merge_start.push_back((int32_t)t);
+        pl.merge_start.push_back((int32_t)pl.merge_tiles.size());
         acc_b = 0;
       }
+      pl.merge_tiles.push_back((int32_t)t);
       acc_b += b;
     }
-    pl.merge_start.push_back((int32_t)pl.tile_base.size() - 1);
+    pl.merge_start.push_back((int32_t)pl.merge_tiles.size());
   }
   pl.off_work = 256;
   pl.off_tiles = pl.off_work + n_items * sizeof(WorkItem);
   pl.off_tile_base = pl.off_tiles + n_tiles * 16;
   pl.off_order = pl.off_tile_base + (n_tiles + 1) * 4;
-  pl.upload_bytes = pl.off_order + n_items * 4;
+  pl.off_merge_tiles = pl.off_order + n_items * 4;
+  pl.upload_bytes = pl.off_merge_tiles + pl.merge_tiles.size() * 4;
   // Workgroups start in grid order: the longest items of a slice go first so that the short ones fill
   // the tail.  Results are stored by item id, so the order is invisible outside the kernel.
   pl.order.resize(n_items);
@@ -529,6 +578,7 @@ int kv_prefill_bind(vkv_pool* p, void* workspace, uint64_t workspace_bytes, void
   std::memcpy(h + p->pf.off_tiles, p->pf.tiles.data(), p->pf.tiles.size() * 4);
   std::memcpy(h + p->pf.off_tile_base, p->pf.tile_base.data(), p->pf.tile_base.size() * 4);
   std::memcpy(h + p->pf.off_order, p->pf.order.data(), p->pf.order.size() * 4);
+  std::memcpy(h + p->pf.off_merge_tiles, p->pf.merge_tiles.data(), p->pf.merge_tiles.size() * 4);
   VKV_HIP(hipMemcpyAsync(workspace, h, p->pf.upload_bytes, hipMemcpyHostToDevice, (hipStream_t)stream));
   VKV_HIP(hipEventRecord(p->stage_ev, (hipStream_t)stream));
   p->stage_inflight = true;

@@ -102,8 +102,9 @@ struct vkv_pool {
     std::vector<int32_t> tiles;            // [n_tiles][4] = (sequence, first q row, first position, positions)
     std::vector<int32_t> tile_base;        // first item of each tile (+1 sentinel)
     std::vector<int32_t> order;            // launch order of the items (a permutation within each slice)
-    std::vector<int32_t> merge_start;      // first tile of each merge step (+1 sentinel)
-    uint64_t off_work = 0, off_tiles = 0, off_tile_base = 0, off_order = 0, off_ml = 0, off_acc = 0, upload_bytes = 0, total = 0;
+    std::vector<int32_t> merge_tiles;      // tiles with more than one chunk, rising
+    std::vector<int32_t> merge_start;      // first entry of merge_tiles of each merge step (+1 sentinel)
+    uint64_t off_work = 0, off_tiles = 0, off_tile_base = 0, off_order = 0, off_merge_tiles = 0, off_ml = 0, off_acc = 0, upload_bytes = 0, total = 0;
   } pf;
 
   // pinned staging (allocated on first device use)

@@ -87,7 +87,7 @@ def main():
                     help="do not bracket launches with timing events (roofline fields become null)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
+        print("bench.py: this library runs on one GPU only (no sharding, no collectives); use --gpus 1",
               file=sys.stderr)
         sys.exit(2)
 

@@ -19,7 +19,7 @@ a library fp64 scaled-dot-product routine, by closed forms and invariances;
 reclamation by a dictionary-based simulator and by conservation invariants;
 Algorithm 1 by exhaustive enumeration of its greedy choice on small instances.
 The pairing rule of relocation (i-th live source, ascending, goes to the i-th
-free destination, ascending) and the pool layout are choices of this build,
+free destination, ascending) and the pool layout are choices of this library,
 not of the paper: for them parity is oracle-defined (pinned only by the
 brute-force simulator and the invariants), i.e. "parity unpinned" by the paper.
 """

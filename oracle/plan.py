@@ -2,7 +2,7 @@
 
 The paper requires offline compute to stop within a bounded, sub-millisecond
 time (Section 2.3, Challenge 1; Section 4.1) without waiting for kernel, layer
-or iteration boundaries.  This build meets that bound cooperatively: the
+or iteration boundaries.  This library meets that bound cooperatively: the
 attention of one layer is cut into slices that each read at most `slice_bytes`
 of KV, and a yield lands between two slices.  This module states which work
 goes into which slice.

@@ -5,11 +5,11 @@ memory reclamation"): when the online tenant needs memory, a set of the offline
 tenant's equal-size handles must be handed over promptly, without the offline
 job touching reclaimed memory afterwards and without killing it.  The paper
 makes the handles harmless by remapping them and lets the framework recompute
-the lost KV; this build keeps the KV instead: every live block inside the
+the lost KV; this library keeps the KV instead: every live block inside the
 range is copied to a free block outside it and every block-table entry that
 named it is rewritten, so the offline job reads the same bytes as before.
 
-Rule that makes the result unique (a choice of this build): the i-th live
+Rule that makes the result unique (a choice of this library): the i-th live
 block of the range in ascending id order moves to the i-th free block, in
 ascending id order, that lies outside the range and outside every range
 already handed over.

@@ -13,7 +13,7 @@ def pytest_configure(config):
 
 
 def pytest_collection_modifyitems(config, items):
-    # GPU tests are only meaningful when selected explicitly on a GPU machine.
+    # GPU tests are only meaningful when selected explicitly on a machine with a GPU.
     try:
         import torch
         has_gpu = torch.cuda.is_available()

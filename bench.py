@@ -65,6 +65,9 @@ def main():
     ap.add_argument("--rate-cap", type=float, default=None, help="bytes/s for the concurrent leg")
     ap.add_argument("--overlap-slices", action="store_true",
                     help="alternate the slices of a layer between two streams (kv_sched_set_overlap)")
+    ap.add_argument("--arena", action="store_true",
+                    help="pool memory from a handle-backed arena; the burst leg then unmaps the handed-over range "
+                         "(physical memory back to the driver) and maps it again when the range is returned")
     ap.add_argument("--bursts", type=int, default=0,
                     help="extra leg: this many online bursts (yield, reclaim, hold, return) at exponential "
                          "inter-arrival times while decode runs continuously")
@@ -125,7 +128,13 @@ def main():
     # ---- inputs, resident in HBM before anything is timed --------------------------
     t_setup = time.time()
     st = synth.build_state(wl, args.seed, materialize_pool=False)
-    pool_t = torch.empty(g.pool_elems, dtype=torch.int16, device=dev)
+    arena = None
+    if args.arena:
+        arena, span = vkv.kv_arena_create(0, g.blocks_per_handle * g.block_bytes, g.num_blocks // g.blocks_per_handle)
+        pool_t = torch.as_tensor(span, device=dev)          # aliases the arena's address range, no copy
+        assert pool_t.data_ptr() == span.address and pool_t.numel() == g.pool_elems
+    else:
+        pool_t = torch.empty(g.pool_elems, dtype=torch.int16, device=dev)
     progress(f"filling the {g.pool_bytes / 2**30:.0f} GiB pool on the device")
     fill_step = 1 << 33                                   # elements per progress line (16 GiB)
     for lo_e in range(0, g.pool_elems, fill_step):
@@ -142,6 +151,8 @@ def main():
     pool = vkv.kv_pool_init(g.num_layers, g.num_q_heads, g.num_kv_heads, g.head_dim, g.num_blocks,
                             g.blocks_per_handle, base=pool_t)
     vkv.kv_pool_adopt(pool, np.flatnonzero(st.live).astype(np.int32))
+    if arena is not None:
+        vkv.kv_pool_attach_arena(pool, arena)
     if args.overlap_slices:
         vkv.kv_sched_set_overlap(pool, True)
     info = vkv.kv_attn_plan(pool, st.ctx_len, slice_bytes, chunk_tokens)
@@ -438,10 +449,24 @@ def main():
                     layer, cur = (layer + 1) % L, 0
             decode_stream.synchronize()
 
-        def give_back():
+        blocks_v = pool_t.view(g.num_blocks, g.block_elems)
+        src_dev = torch.from_numpy(src_ids).to(dev).long()
+        dst_dev = torch.from_numpy(dst_ids).to(dev).long()
+        unmap_ms, map_ms = [], []
+
+        def give_back(unmapped=False):
+            if unmapped:
+                t_m = time.perf_counter()
+                vkv.kv_arena_restore(arena, pool, lo, hi)
+                map_ms.append((time.perf_counter() - t_m) * 1e3)
             vkv.kv_pool_return_range(pool, lo, hi)
             vkv.kv_pool_free(pool, dst_ids)
             vkv.kv_pool_adopt(pool, src_ids)
+            if unmapped:
+                # the range came back with fresh memory: the offline tenant's blocks move back in
+                with torch.cuda.stream(copy_stream):
+                    for i in range(0, len(src_ids), 1024):
+                        blocks_v[src_dev[i:i + 1024]] = blocks_v[dst_dev[i:i + 1024]]
             with torch.cuda.stream(copy_stream):
                 tables.copy_(tables0)
             copy_stream.synchronize()
@@ -476,13 +501,16 @@ def main():
                 progress("    offline compute is off the GPU; reclaiming")
             vkv.kv_reclaim_range(pool, lo, hi, tables, remap, chunk_bytes=rc_chunk, copy_stream=copy_stream,
                                  decode_stream=decode_stream)
-            t_rel = time.perf_counter()
+            t_rel = time.perf_counter()      # handed over: a tenant in this process may use the range now
+            if arena is not None:
+                vkv.kv_arena_release(arena, pool, lo, hi)     # the physical memory is the driver's again
+                unmap_ms.append((time.perf_counter() - t_rel) * 1e3)
             to_idle.append((t_idle - t_req) * 1e3)
             to_released.append((t_rel - min(t_arr, t_req)) * 1e3)
             if verbose:
                 progress("    range handed over; online tenant holds it")
             time.sleep(args.burst_hold_ms * 1e-3)
-            give_back()
+            give_back(unmapped=arena is not None)
             vkv.kv_yield_clear(pool)
             paused += time.perf_counter() - t_req
             with cv:
@@ -507,6 +535,11 @@ def main():
             "burst_decode_GBps_whole_run": round(layers_done[0] * decode_bytes_layer / total_s / 1e9, 1),
             "burst_decode_GBps_while_running": round(layers_done[0] * decode_bytes_layer / (total_s - paused) / 1e9, 1),
         })
+        if arena is not None:
+            extra.update({"burst_unmap_ms_p50": round(percentile(unmap_ms, 50), 3),
+                          "burst_unmap_ms_p99": round(percentile(unmap_ms, 99), 3),
+                          "burst_map_ms_p50": round(percentile(map_ms, 50), 3),
+                          "burst_map_ms_p99": round(percentile(map_ms, 99), 3)})
 
     # ---- optional: preemptible causal prefill over the same pool (MFMA-bound) -------------
     if args.prefill_leg:
@@ -598,6 +631,9 @@ def main():
         workers.join()
 
     vkv.kv_pool_destroy(pool)
+    if arena is not None:
+        del pool_t
+        vkv.kv_arena_destroy(arena)
     line = {
         "metric": "reclaim GB/s & paged-decode GB/s (% HBM peak); p99 yield latency us",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -608,7 +644,8 @@ def main():
                                 f"occupancy={wl.occupancy} reclaim_top={(hi - lo) * g.block_bytes / 2**30:.2f}GiB"),
                    "chunk_tokens": chunk_tokens, "slice_bytes": slice_bytes, "n_slices_per_layer": info.n_slices,
                    "n_items_per_layer": info.n_items, "reclaim_chunk_bytes": rc_chunk,
-                   "max_inflight": args.max_inflight, "overlap_slices": bool(args.overlap_slices), "seed": args.seed},
+                   "max_inflight": args.max_inflight, "overlap_slices": bool(args.overlap_slices),
+                   "arena": bool(args.arena), "seed": args.seed},
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
         "step_bytes": step_bytes, "decode_bytes": decode_bytes, "reclaim_traffic_bytes": reclaim_traffic,
         "setup_s": round(setup_s, 1),

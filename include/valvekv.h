@@ -425,6 +425,53 @@ int kv_profile_enable(vkv_pool* pool, int32_t max_records);
  * order) to out_host, their count to *n_out, and restarts recording at zero. */
 int kv_profile_read(vkv_pool* pool, vkv_profile_record* out_host, int32_t cap, int32_t* n_out);
 
+/* ---- handle-backed pool memory (optional) ------------------------------------
+ * The paper allocates and releases KV memory in equal-size handles and a
+ * reclaimed handle leaves the offline job for good (Section 5).  An arena is
+ * one reservation of device address space of num_handles * handle_bytes with
+ * one physical allocation per handle (HIP virtual-memory API).  Used as the
+ * pool's memory, it lets a range that kv_reclaim_range has handed over be
+ * unmapped, which returns its physical memory to the driver: any other
+ * allocation on the device, another process's included, can then have it.
+ * Giving the range back maps fresh memory at the same addresses, so block ids
+ * and tables stay as they are.  These are the only calls that allocate device
+ * memory, and only at the caller's request.  Memory thread. */
+typedef struct vkv_arena vkv_arena;
+
+/* Reserves the address range on `device` and backs every handle.  *base_out is
+ * the device address to use as vkv_pool_config.base (bytes = num_handles *
+ * handle_bytes; handle_bytes = blocks_per_handle * block bytes, a multiple of
+ * the allocation granularity, 4 KiB here).
+ * Errors: VKV_E_INVAL, VKV_E_NOSPACE (device memory), VKV_E_HIP. */
+int kv_arena_create(int32_t device, uint64_t handle_bytes, int32_t num_handles, vkv_arena** arena_out,
+                    void** base_out);
+/* Unmaps what is mapped and frees the reservation.  Destroy the pool first. */
+int kv_arena_destroy(vkv_arena* arena);
+
+/* Tells the pool that its memory is this arena (NULL detaches).  Checks base,
+ * handle size and total size.  With an arena attached, kv_pool_return_range
+ * refuses (VKV_E_STATE) a range whose handles are unmapped. */
+int kv_pool_attach_arena(vkv_pool* pool, vkv_arena* arena);
+
+/* Unmaps the handles of [lo_block, hi_block) and releases their physical
+ * memory.  The range must be one that kv_reclaim_range (or
+ * kv_invalidate_handles) has handed over and that has not been returned: by
+ * then the copy, the table rewrite and the grace wait are over, and the
+ * allocator, the planner and every block table avoid it.  Any later access to
+ * it is a GPU fault.  Errors: VKV_E_INVAL (arena not attached to this pool),
+ * VKV_E_STATE (not a handed-over range, or already unmapped), VKV_E_HIP. */
+int kv_arena_release(vkv_arena* arena, vkv_pool* pool, int32_t lo_block, int32_t hi_block);
+
+/* Maps fresh physical memory (contents undefined) behind the handles of a
+ * handed-over, unmapped range; follow with kv_pool_return_range.  On failure
+ * the whole range stays unmapped.  Errors: VKV_E_INVAL, VKV_E_STATE,
+ * VKV_E_NOSPACE (the device has no memory left), VKV_E_HIP. */
+int kv_arena_restore(vkv_arena* arena, vkv_pool* pool, int32_t lo_block, int32_t hi_block);
+
+/* mapped_out_host[num_handles] (1 = backed by physical memory), may be NULL;
+ * *mapped_bytes_out = bytes currently backed, may be NULL. */
+int kv_arena_state(vkv_arena* arena, uint8_t* mapped_out_host, uint64_t* mapped_bytes_out);
+
 /* ---- bandwidth yardsticks ---------------------------------------------------
  * Not part of the method: the attention and relocation kernels are bound by
  * HBM bandwidth, and these two calls measure what the memory system gives the

@@ -26,6 +26,8 @@ __all__ = [
     "kv_select_handles", "kv_invalidate_handles", "MiadConfig", "MiadStep", "kv_miad_init", "kv_miad_destroy",
     "kv_miad_observe", "kv_gate_init", "kv_gate_destroy", "kv_gate_online_busy", "kv_gate_online_idle",
     "kv_gate_poll", "kv_gate_stats", "kv_probe_read", "kv_probe_copy", "kv_probe_attn_reads", "kv_sched_set_overlap",
+    "kv_arena_create", "kv_arena_destroy", "kv_pool_attach_arena", "kv_arena_release", "kv_arena_restore",
+    "kv_arena_state", "DeviceSpan",
 ]
 
 VKV_OK, VKV_YIELDED = 0, 1
@@ -142,6 +144,12 @@ _sigs = {
     "kv_profile_enable": (C.c_int, [_P, C.c_int32]),
     "kv_profile_read": (C.c_int, [_P, _P, C.c_int32, _I32P]),
     "kv_sched_set_overlap": (C.c_int, [_P, C.c_int32]),
+    "kv_arena_create": (C.c_int, [C.c_int32, C.c_uint64, C.c_int32, C.POINTER(_P), C.POINTER(_P)]),
+    "kv_arena_destroy": (C.c_int, [_P]),
+    "kv_pool_attach_arena": (C.c_int, [_P, _P]),
+    "kv_arena_release": (C.c_int, [_P, _P, C.c_int32, C.c_int32]),
+    "kv_arena_restore": (C.c_int, [_P, _P, C.c_int32, C.c_int32]),
+    "kv_arena_state": (C.c_int, [_P, _P, C.POINTER(C.c_uint64)]),
     "kv_probe_read": (C.c_int, [_P, C.c_uint64, _P, _P]),
     "kv_probe_attn_reads": (C.c_int, [_P, C.c_int32, C.c_int32, _P, C.c_int32, _P, _P, _P]),
     "kv_probe_copy": (C.c_int, [_P, _P, C.c_uint64, _P]),
@@ -329,6 +337,48 @@ def kv_profile_read(pool, cap: int) -> np.ndarray:
 
 def kv_sched_set_overlap(pool, enable: bool):
     _check(lib.kv_sched_set_overlap(pool, 1 if enable else 0))
+
+
+# ---- handle-backed pool memory ----------------------------------------------------
+class DeviceSpan:
+    """A raw device address range as an object torch can alias without copying
+    (`torch.as_tensor(span, device="cuda")` gives an int16 tensor over it)."""
+
+    def __init__(self, address: int, nbytes: int):
+        self.address, self.nbytes = address, nbytes
+        self.__cuda_array_interface__ = {"shape": (nbytes // 2,), "typestr": "<i2", "data": (address, False),
+                                         "version": 2, "strides": None}
+
+
+def kv_arena_create(device: int, handle_bytes: int, num_handles: int):
+    """Returns (arena handle, DeviceSpan of the whole address range)."""
+    arena, base = _P(), _P()
+    _check(lib.kv_arena_create(device, handle_bytes, num_handles, C.byref(arena), C.byref(base)))
+    return arena, DeviceSpan(base.value, handle_bytes * num_handles)
+
+
+def kv_arena_destroy(arena):
+    _check(lib.kv_arena_destroy(arena))
+
+
+def kv_pool_attach_arena(pool, arena):
+    _check(lib.kv_pool_attach_arena(pool, arena))
+
+
+def kv_arena_release(arena, pool, lo: int, hi: int):
+    _check(lib.kv_arena_release(arena, pool, lo, hi))
+
+
+def kv_arena_restore(arena, pool, lo: int, hi: int):
+    _check(lib.kv_arena_restore(arena, pool, lo, hi))
+
+
+def kv_arena_state(arena, num_handles: int):
+    """Returns (mapped uint8[num_handles], bytes currently backed)."""
+    m = np.zeros(num_handles, dtype=np.uint8)
+    n = C.c_uint64(0)
+    _check(lib.kv_arena_state(arena, m.ctypes.data, C.byref(n)))
+    return m, n.value
 
 
 # ---- bandwidth yardsticks ---------------------------------------------------------

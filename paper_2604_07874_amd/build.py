@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvalvekv.so")
-SOURCES = ["pool.hip", "attn.hip", "reclaim.hip", "policy.hip", "prefill.hip", "probe.hip"]
+SOURCES = ["pool.hip", "attn.hip", "reclaim.hip", "policy.hip", "prefill.hip", "probe.hip", "arena.hip"]
 DRIVER = os.path.join(HERE, "vkv_pmc_driver")
 
 

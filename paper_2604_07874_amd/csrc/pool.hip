@@ -186,6 +186,10 @@ int kv_pool_return_range(vkv_pool* p, int32_t lo, int32_t hi) {
   if (!p) { set_error("kv_pool_return_range: null pool"); return VKV_E_INVAL; }
   for (size_t i = 0; i < p->released.size(); ++i) {
     if (p->released[i].first == lo && p->released[i].second == hi) {
+      if (p->arena && !arena_range_mapped(p->arena, lo / p->cfg.blocks_per_handle, hi / p->cfg.blocks_per_handle)) {
+        set_error("kv_pool_return_range: handles of [%d,%d) are unmapped; kv_arena_restore first", lo, hi);
+        return VKV_E_STATE;
+      }
       p->released.erase(p->released.begin() + (long)i);
       return VKV_OK;
     }

@@ -64,8 +64,11 @@ inline WorkspaceLayout workspace_layout(int64_t n_items, int64_t num_seqs, int H
 
 }  // namespace vkv
 
+struct vkv_arena;
+
 struct vkv_pool {
   vkv_pool_config cfg{};
+  const vkv_arena* arena = nullptr;   // handle-backed memory under the pool, if the caller attached one
   int G = 1;
   uint64_t block_elems = 0;   // bf16 elements per block
   uint64_t block_bytes = 0;
@@ -165,6 +168,8 @@ struct ProfScope {
 };
 
 // Slice scheduler shared by decode and prefill (attn.hip).
+// true if handles [first, last) of the arena all have physical memory behind them
+bool arena_range_mapped(const vkv_arena* a, int32_t first, int32_t last);
 int run_slices(vkv_pool* p, int32_t* cursor, int32_t n_slices, int32_t max_inflight, hipStream_t hs, const char* who,
                const std::function<int(int32_t, hipStream_t)>& launch, int32_t n_tail,
                const std::function<int(int32_t)>& tail);

@@ -73,8 +73,10 @@ def main():
                          "inter-arrival times while decode runs continuously")
     ap.add_argument("--burst-mean-s", type=float, default=0.2)
     ap.add_argument("--burst-hold-ms", type=float, default=20.0)
-    ap.add_argument("--prefill-leg", action="store_true",
-                    help="extra leg: causal prefill of the newest --prefill-tokens tokens of every sequence")
+    ap.add_argument("--prefill-leg", dest="prefill_leg", action="store_true", default=None,
+                    help="extra leg: causal prefill of the newest --prefill-tokens tokens of every sequence "
+                         "(default: on for the llama8b workload)")
+    ap.add_argument("--no-prefill-leg", dest="prefill_leg", action="store_false")
     ap.add_argument("--prefill-tokens", type=int, default=2048)
     ap.add_argument("--prefill-slice-bytes", type=int, default=512 << 20)
     ap.add_argument("--prefill-one-stream", action="store_true",
@@ -120,6 +122,8 @@ def main():
 
     wl = synth.workload(args.workload)
     g = wl.geom
+    if args.prefill_leg is None:
+        args.prefill_leg = wl.name == "llama8b"
     chunk_tokens = args.chunk_tokens or wl.chunk_tokens
     slice_bytes = args.slice_bytes or wl.slice_bytes
     rc_chunk = wl.chunk_bytes if args.reclaim_chunk_bytes is None else args.reclaim_chunk_bytes
@@ -543,82 +547,87 @@ def main():
 
     # ---- optional: preemptible causal prefill over the same pool (MFMA-bound) -------------
     if args.prefill_leg:
-        q_len = np.minimum(st.ctx_len, args.prefill_tokens).astype(np.int32)
-        pinfo = vkv.kv_prefill_plan(pool, st.ctx_len, q_len, args.prefill_slice_bytes, args.prefill_chunk_tokens)
-        pws = torch.empty(pinfo.workspace_bytes, dtype=torch.uint8, device=dev)
-        vkv.kv_prefill_bind(pool, pws, stream)
-        pq = torch.empty((pinfo.total_q, g.num_q_heads, g.head_dim), dtype=torch.int16, device=dev)
-        # query values: the generator's bits at the start of the pool serve as well as any
-        pq.view(-1).copy_(pool_t[:pq.numel()])
-        pout = torch.empty((pinfo.total_q, g.num_q_heads, g.head_dim), dtype=torch.float32, device=dev)
-        p_overlap = not args.prefill_one_stream
-        vkv.kv_sched_set_overlap(pool, p_overlap)
-        vkv.kv_profile_enable(pool, (pinfo.n_slices + pinfo.n_merge_steps) * 3 + 16)
-        n_layers_p = min(L, 2)
-        for layer in range(n_layers_p):           # warm-up
-            vkv.kv_prefill_run_layer(pool, layer, 0, pq, tables, pws, pout, max_inflight=args.max_inflight, stream=stream)
-        torch.cuda.synchronize()
-        vkv.kv_profile_read(pool, 1 << 20)
-        t0 = time.perf_counter()
-        for layer in range(n_layers_p):
-            vkv.kv_prefill_run_layer(pool, layer, 0, pq, tables, pws, pout, max_inflight=args.max_inflight, stream=stream)
-        torch.cuda.synchronize()
-        dt = (time.perf_counter() - t0) / n_layers_p
-        rec = vkv.kv_profile_read(pool, 1 << 20)
-        psl = rec[rec["kind"] == vkv.VKV_PROF_PREFILL]
-        pmg = rec[rec["kind"] == vkv.VKV_PROF_PREFILL_MERGE]
-        vkv.kv_profile_enable(pool, 0)
-        # overlapped launches: per-launch durations are not additive, rate by the wall clock instead
-        kern_s = dt if p_overlap else float(psl["ms"].sum()) * 1e-3 / n_layers_p
-        extra.update({
-            "prefill_rows": int(pinfo.total_q), "prefill_slices_per_layer": int(pinfo.n_slices),
-            "prefill_items_per_layer": int(pinfo.n_items), "prefill_merge_steps_per_layer": int(pinfo.n_merge_steps),
-            "prefill_overlapped_slices": p_overlap,
-            "prefill_slice_bytes": args.prefill_slice_bytes, "prefill_chunk_tokens": args.prefill_chunk_tokens,
-            "prefill_TFLOPs_wall": round(pinfo.flops_per_layer / dt / 1e12, 1),
-            "prefill_TFLOPs_kernel": None if p_overlap else round(pinfo.flops_per_layer / kern_s / 1e12, 1),
-            "prefill_frac_of_mfma_bf16_peak": round(pinfo.flops_per_layer / kern_s / 2.5e15, 4),
-            "prefill_ms_per_layer": round(dt * 1e3, 3),
-            "prefill_slice_us_p50": round(percentile(psl["ms"], 50) * 1e3, 1),
-            "prefill_slice_us_p99": round(percentile(psl["ms"], 99) * 1e3, 1),
-            "prefill_kv_GBps": round(pinfo.kv_bytes_per_layer / kern_s / 1e9, 1),
-            "prefill_merge_us_per_layer": round(float(pmg["ms"].sum()) * 1e3 / n_layers_p, 1),
-            "prefill_merge_step_us_max": round(float(pmg["ms"].max()) * 1e3, 1) if len(pmg) else None,
-        })
-        # yield latency of a prefill: request at a random instant of a layer, until compute is off the GPU
-        if args.prefill_yield_injections > 0:
-            prng = np.random.default_rng(args.seed + 2)
-            plat, preq = [], [0.0]
-
-            def prequester(delay):
-                time.sleep(delay)
-                preq[0] = time.perf_counter()
-                vkv.kv_yield_request(pool)
-
-            layer, cur, t_begin = 0, 0, time.time()
-            for _ in range(args.prefill_yield_injections):
-                if time.time() - t_begin > 40.0:
-                    break
-                th = threading.Thread(target=prequester, args=(float(prng.uniform(0.0, dt)),))
-                th.start()
-                landed = None
-                while landed is None:
-                    s_, cur = vkv.kv_prefill_run_layer(pool, layer, cur, pq, tables, pws, pout,
-                                                       max_inflight=args.max_inflight, stream=stream)
-                    if s_ == vkv.VKV_YIELDED:
-                        landed = time.perf_counter()
-                    else:
-                        layer, cur = (layer + 1) % n_layers_p, 0
-                th.join()
-                plat.append((landed - preq[0]) * 1e6)
-                vkv.kv_yield_clear(pool)
+        progress("prefill leg")
+        try:
+            q_len = np.minimum(st.ctx_len, args.prefill_tokens).astype(np.int32)
+            pinfo = vkv.kv_prefill_plan(pool, st.ctx_len, q_len, args.prefill_slice_bytes, args.prefill_chunk_tokens)
+            pws = torch.empty(pinfo.workspace_bytes, dtype=torch.uint8, device=dev)
+            vkv.kv_prefill_bind(pool, pws, stream)
+            pq = torch.empty((pinfo.total_q, g.num_q_heads, g.head_dim), dtype=torch.int16, device=dev)
+            # query values: the generator's bits at the start of the pool serve as well as any
+            pq.view(-1).copy_(pool_t[:pq.numel()])
+            pout = torch.empty((pinfo.total_q, g.num_q_heads, g.head_dim), dtype=torch.float32, device=dev)
+            p_overlap = not args.prefill_one_stream
+            vkv.kv_sched_set_overlap(pool, p_overlap)
+            vkv.kv_profile_enable(pool, (pinfo.n_slices + pinfo.n_merge_steps) * 3 + 16)
+            n_layers_p = min(L, 2)
+            for layer in range(n_layers_p):           # warm-up
+                vkv.kv_prefill_run_layer(pool, layer, 0, pq, tables, pws, pout, max_inflight=args.max_inflight, stream=stream)
             torch.cuda.synchronize()
-            extra.update({"prefill_yield_latency_us_p50": round(percentile(plat, 50), 1),
-                          "prefill_yield_latency_us_p99": round(percentile(plat, 99), 1),
-                          "prefill_yield_latency_us_max": round(max(plat), 1), "prefill_yield_injections": len(plat)})
-        vkv.kv_prefill_check(pool, pws, stream)
-        vkv.kv_sched_set_overlap(pool, bool(args.overlap_slices))
-        del pws, pq, pout
+            vkv.kv_profile_read(pool, 1 << 20)
+            t0 = time.perf_counter()
+            for layer in range(n_layers_p):
+                vkv.kv_prefill_run_layer(pool, layer, 0, pq, tables, pws, pout, max_inflight=args.max_inflight, stream=stream)
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) / n_layers_p
+            rec = vkv.kv_profile_read(pool, 1 << 20)
+            psl = rec[rec["kind"] == vkv.VKV_PROF_PREFILL]
+            pmg = rec[rec["kind"] == vkv.VKV_PROF_PREFILL_MERGE]
+            vkv.kv_profile_enable(pool, 0)
+            # overlapped launches: per-launch durations are not additive, rate by the wall clock instead
+            kern_s = dt if p_overlap else float(psl["ms"].sum()) * 1e-3 / n_layers_p
+            extra.update({
+                "prefill_rows": int(pinfo.total_q), "prefill_slices_per_layer": int(pinfo.n_slices),
+                "prefill_items_per_layer": int(pinfo.n_items), "prefill_merge_steps_per_layer": int(pinfo.n_merge_steps),
+                "prefill_overlapped_slices": p_overlap,
+                "prefill_slice_bytes": args.prefill_slice_bytes, "prefill_chunk_tokens": args.prefill_chunk_tokens,
+                "prefill_TFLOPs_wall": round(pinfo.flops_per_layer / dt / 1e12, 1),
+                "prefill_TFLOPs_kernel": None if p_overlap else round(pinfo.flops_per_layer / kern_s / 1e12, 1),
+                "prefill_frac_of_mfma_bf16_peak": round(pinfo.flops_per_layer / kern_s / 2.5e15, 4),
+                "prefill_ms_per_layer": round(dt * 1e3, 3),
+                "prefill_slice_us_p50": round(percentile(psl["ms"], 50) * 1e3, 1),
+                "prefill_slice_us_p99": round(percentile(psl["ms"], 99) * 1e3, 1),
+                "prefill_kv_GBps": round(pinfo.kv_bytes_per_layer / kern_s / 1e9, 1),
+                "prefill_merge_us_per_layer": round(float(pmg["ms"].sum()) * 1e3 / n_layers_p, 1),
+                "prefill_merge_step_us_max": round(float(pmg["ms"].max()) * 1e3, 1) if len(pmg) else None,
+            })
+            # yield latency of a prefill: request at a random instant of a layer, until compute is off the GPU
+            if args.prefill_yield_injections > 0:
+                prng = np.random.default_rng(args.seed + 2)
+                plat, preq = [], [0.0]
+
+                def prequester(delay):
+                    time.sleep(delay)
+                    preq[0] = time.perf_counter()
+                    vkv.kv_yield_request(pool)
+
+                layer, cur, t_begin = 0, 0, time.time()
+                for _ in range(args.prefill_yield_injections):
+                    if time.time() - t_begin > 40.0:
+                        break
+                    th = threading.Thread(target=prequester, args=(float(prng.uniform(0.0, dt)),))
+                    th.start()
+                    landed = None
+                    while landed is None:
+                        s_, cur = vkv.kv_prefill_run_layer(pool, layer, cur, pq, tables, pws, pout,
+                                                           max_inflight=args.max_inflight, stream=stream)
+                        if s_ == vkv.VKV_YIELDED:
+                            landed = time.perf_counter()
+                        else:
+                            layer, cur = (layer + 1) % n_layers_p, 0
+                    th.join()
+                    plat.append((landed - preq[0]) * 1e6)
+                    vkv.kv_yield_clear(pool)
+                torch.cuda.synchronize()
+                extra.update({"prefill_yield_latency_us_p50": round(percentile(plat, 50), 1),
+                              "prefill_yield_latency_us_p99": round(percentile(plat, 99), 1),
+                              "prefill_yield_latency_us_max": round(max(plat), 1), "prefill_yield_injections": len(plat)})
+            vkv.kv_prefill_check(pool, pws, stream)
+            vkv.kv_sched_set_overlap(pool, bool(args.overlap_slices))
+            del pws, pq, pout
+        except Exception as e:      # an extra leg must not take the headline line down with it
+            extra["prefill_error"] = f"{type(e).__name__}: {e}"
+            vkv.kv_yield_clear(pool)
 
     progress("CPU oracle baseline")
     # ---- the CPU oracle on a bounded sample of the same workload --------------------

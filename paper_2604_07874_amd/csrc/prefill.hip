@@ -280,42 +280,48 @@ __global__ __launch_bounds__(256, 2) void paged_prefill_attn_slice_kernel(const 
   }
 }
 
-// Merge of the chunks of one split (tile, kv head): log-sum-exp merge in chunk order.
-// Pass 1, one thread per column: the maximum over the chunks, then the chunk weights
-// 2^(m_c - M) into LDS (32 chunks at a time) and their weighted sum of the partial sums.
-// Pass 2, one thread per (column, four output dims): the weighted partial accumulators, with
-// the loads of four chunks in flight at a time, since this kernel is nothing but memory latency.
+// Merge of the chunks of one split (tile, kv head): log-sum-exp merge in chunk order.  A workgroup
+// takes a quarter of the tile's columns (kMergeCols), so that a merge step has four times the
+// workgroups and a quarter of the dependent loads per thread: the kernel is nothing but memory latency.
+// Pass 1, one thread per column: the maximum over the chunks, then the chunk weights 2^(m_c - M)
+// into LDS (32 chunks at a time) and their weighted sum of the partial sums.
+// Pass 2, one thread per (column, four output dims): the weighted partial accumulators, with the
+// loads of four chunks in flight at a time.
+constexpr int kMergeCols = 32;
 template <int D>
 __global__ __launch_bounds__(256) void prefill_merge_kernel(const PrefillParams p) {
   constexpr int kBatch = 32;
-  __shared__ float sm_w[kBatch][kTileColumns];
-  __shared__ float sm_M[kTileColumns], sm_den[kTileColumns];
+  constexpr int kParts = kTileColumns / kMergeCols;
+  __shared__ float sm_w[kBatch][kMergeCols];
+  __shared__ float sm_M[kMergeCols], sm_den[kMergeCols];
   // item_first = first entry of the step in the list of split tiles
-  const int tile = p.merge_tiles[p.item_first + blockIdx.x / p.Hkv], head = blockIdx.x % p.Hkv;
+  const int unit = blockIdx.x / kParts, col0 = (blockIdx.x % kParts) * kMergeCols;
+  const int tile = p.merge_tiles[p.item_first + unit / p.Hkv], head = unit % p.Hkv;
   const int base = p.tile_base[tile];
   const int nch = (p.tile_base[tile + 1] - base) / p.Hkv;
   const int row0 = p.tiles[4 * tile + 1], n_pos = p.tiles[4 * tile + 3];
   const int G = p.G, gp_mask = (1 << p.gp_shift) - 1;
   auto item_col = [&](int c, int col) { return ((size_t)base + (size_t)c * p.Hkv + head) * kTileColumns + col; };
   const int tid = threadIdx.x;
-  if (tid < kTileColumns) {
+  if (tid < kMergeCols) {
     float M = -INFINITY;
-    for (int c = 0; c < nch; ++c) M = fmaxf(M, p.part_ml[item_col(c, tid) * 2]);
+    for (int c = 0; c < nch; ++c) M = fmaxf(M, p.part_ml[item_col(c, col0 + tid) * 2]);
     sm_M[tid] = M;
     sm_den[tid] = 0.f;
   }
   constexpr int VPR = D / 4;                         // float4 per column
-  f32x4 num[kTileColumns * VPR / 256];
+  constexpr int kIters = kMergeCols * VPR / 256;
+  f32x4 num[kIters];
 #pragma unroll
-  for (int i = 0; i < kTileColumns * VPR / 256; ++i) num[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int i = 0; i < kIters; ++i) num[i] = f32x4{0.f, 0.f, 0.f, 0.f};
   for (int c0 = 0; c0 < nch; c0 += kBatch) {
     const int nb = min(kBatch, nch - c0);
     __syncthreads();                                 // sm_M ready / previous batch's weights consumed
-    if (tid < kTileColumns) {
+    if (tid < kMergeCols) {
       const float M = sm_M[tid];
       float den = sm_den[tid];
       for (int j = 0; j < nb; ++j) {
-        const size_t ic = item_col(c0 + j, tid);
+        const size_t ic = item_col(c0 + j, col0 + tid);
         const float wt = __builtin_exp2f(p.part_ml[ic * 2] - M);   // 0 for a chunk this column cannot see
         sm_w[j][tid] = wt;
         den += wt * p.part_ml[ic * 2 + 1];
@@ -324,28 +330,29 @@ __global__ __launch_bounds__(256) void prefill_merge_kernel(const PrefillParams 
     }
     __syncthreads();
 #pragma unroll
-    for (int i = 0; i < kTileColumns * VPR / 256; ++i) {
-      const int e = i * 256 + tid, col = e / VPR, v = e - col * VPR;
+    for (int i = 0; i < kIters; ++i) {
+      const int e = i * 256 + tid, lc = e / VPR, v = e - lc * VPR;
       int j = 0;
       for (; j + 4 <= nb; j += 4) {
         f32x4 x[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u)
-          x[u] = *reinterpret_cast<const f32x4*>(p.part_acc + item_col(c0 + j + u, col) * D + v * 4);
+          x[u] = *reinterpret_cast<const f32x4*>(p.part_acc + item_col(c0 + j + u, col0 + lc) * D + v * 4);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) num[i] += sm_w[j + u][col] * x[u];
+        for (int u = 0; u < 4; ++u) num[i] += sm_w[j + u][lc] * x[u];
       }
       for (; j < nb; ++j)
-        num[i] += sm_w[j][col] * *reinterpret_cast<const f32x4*>(p.part_acc + item_col(c0 + j, col) * D + v * 4);
+        num[i] += sm_w[j][lc] * *reinterpret_cast<const f32x4*>(p.part_acc + item_col(c0 + j, col0 + lc) * D + v * 4);
     }
   }
   __syncthreads();
 #pragma unroll
-  for (int i = 0; i < kTileColumns * VPR / 256; ++i) {
-    const int e = i * 256 + tid, col = e / VPR, v = e - col * VPR;
+  for (int i = 0; i < kIters; ++i) {
+    const int e = i * 256 + tid, lc = e / VPR, v = e - lc * VPR;
+    const int col = col0 + lc;
     const int cpos = col >> p.gp_shift, cg = col & gp_mask;
     if (cg >= G || cpos >= n_pos) continue;
-    const float inv = 1.0f / sm_den[col];
+    const float inv = 1.0f / sm_den[lc];
     *reinterpret_cast<f32x4*>(p.out + ((size_t)(row0 + cpos) * p.Hq + (size_t)head * G + cg) * D + v * 4) = num[i] * inv;
   }
 }
@@ -428,7 +435,8 @@ static int pf_launch_merge(vkv_pool* p, int32_t step, void* workspace, void* out
   const int32_t n_tiles = p->pf.merge_start[step + 1] - a.item_first;
   if (n_tiles == 0) return VKV_OK;   // no tile of this plan was split
   ProfScope prof(p, VKV_PROF_PREFILL_MERGE, step, st);
-  hipLaunchKernelGGL(prefill_merge_kernel<128>, dim3((unsigned)(n_tiles * p->cfg.num_kv_heads)), dim3(256), 0, st, a);
+  hipLaunchKernelGGL(prefill_merge_kernel<128>, dim3((unsigned)(n_tiles * p->cfg.num_kv_heads * (kTileColumns / kMergeCols))),
+                     dim3(256), 0, st, a);
   VKV_HIP(hipGetLastError());
   return VKV_OK;
 }

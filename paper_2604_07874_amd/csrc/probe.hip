@@ -14,13 +14,15 @@ constexpr int kProbeUnroll = 8;         // loads in flight per lane
 // it equals a value the caller cannot have produced on purpose, which keeps the loads alive.
 __global__ __launch_bounds__(256) void probe_read_kernel(const u32x4* __restrict__ src, uint64_t n_vecs,
                                                          u32x4* __restrict__ sink) {
-  const uint64_t first = (uint64_t)blockIdx.x * kProbeVecsPerWg;
+  // each wave streams a contiguous quarter of the piece (requests of a wave follow each other in address)
+  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+  const uint64_t first = (uint64_t)blockIdx.x * kProbeVecsPerWg + wave * (kProbeVecsPerWg / 4);
   u32x4 acc = {0u, 0u, 0u, 0u};
-  for (uint32_t i = threadIdx.x; i < (uint32_t)kProbeVecsPerWg; i += 256 * kProbeUnroll) {
+  for (uint32_t i = lane; i < (uint32_t)kProbeVecsPerWg / 4; i += 64 * kProbeUnroll) {
     u32x4 r[kProbeUnroll];
 #pragma unroll
     for (int u = 0; u < kProbeUnroll; ++u) {
-      const uint64_t idx = first + i + (uint64_t)u * 256;
+      const uint64_t idx = first + i + (uint64_t)u * 64;
       r[u] = idx < n_vecs ? __builtin_nontemporal_load(src + idx) : u32x4{0u, 0u, 0u, 0u};
     }
 #pragma unroll

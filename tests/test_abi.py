@@ -132,3 +132,21 @@ def test_device_entry_points_refuse_a_host_only_pool(vkv):
     st = vkv.lib.paged_decode_attn_slice(p, 0, 0, None, None, 0, None, None, 0.0, None)
     assert st == vkv.VKV_E_STATE       # no plan yet
     vkv.kv_pool_destroy(p)
+
+
+def test_prefill_merge_is_cut_into_bounded_steps(vkv):
+    """Host only: the merge of split tiles is planned as steps whose size follows slice_bytes, one
+    step when nothing is split."""
+    wl = synth.workload("llama8b_small")
+    st = synth.build_state(wl, 5, materialize_pool=False)
+    p = make_pool(vkv, wl, st)
+    try:
+        q_len = np.minimum(st.ctx_len, 4096).astype(np.int32)
+        whole = vkv.kv_prefill_plan(p, st.ctx_len, q_len, 1 << 40, 16384)     # every tile is one chunk
+        assert whole.n_merge_steps == 1 and whole.n_slices == 1
+        coarse = vkv.kv_prefill_plan(p, st.ctx_len, q_len, 64 << 20, 256)
+        fine = vkv.kv_prefill_plan(p, st.ctx_len, q_len, 1 << 20, 256)
+        assert 1 <= coarse.n_merge_steps < fine.n_merge_steps
+        assert fine.n_items == coarse.n_items and fine.n_slices > coarse.n_slices
+    finally:
+        vkv.kv_pool_destroy(p)

@@ -164,3 +164,28 @@ def test_hand_derived_exact_cases_through_the_library():
                 assert np.max(np.abs(got[:q_len[0], head, :d0] - want)) <= TOL * max(1.0, np.abs(want).max()), case["name"]
     finally:
         vkv.kv_pool_destroy(p)
+
+
+def test_context_lengths_on_every_boundary():
+    """Contexts of one token, around a block (16), a group (32), a chunk and the table-window (1024)
+    boundaries, through chunked and unchunked plans."""
+    from gpu_util import DeviceCase, layout_of
+    wl = synth.workload("stress_small", ctx_dist=("uniform", 2049, 2049), num_seqs=10)
+    c = DeviceCase(wl, seed=13)
+    try:
+        g = wl.geom
+        q, q_t = c.q_dev(0)
+        lay = layout_of(g)
+        lengths = [1, 2, 15, 16, 17, 31, 32, 33, 63, 64, 65, 255, 256, 257, 511, 512, 513, 1023, 1024, 1025, 2047, 2048,
+                   2049, 1, 100, 1000, 7, 2000, 48, 1536]
+        assert int(c.st.ctx_len.min()) >= 2049
+        for first in range(0, len(lengths), wl.num_seqs):
+            ctx = np.array(lengths[first:first + wl.num_seqs], dtype=np.int32)
+            want = paged_decode_attention(c.pool_bits, lay, q, c.st.tables, ctx, 0)
+            for chunk, slice_bytes in ((2048, 1 << 30), (256, 1 << 18), (32, 1 << 14)):
+                c.plan(slice_bytes=slice_bytes, chunk_tokens=chunk, ctx=ctx)
+                got = c.attention(0, q_t)
+                err = float(np.max(np.abs(got.astype(np.float64) - want)))
+                assert err <= TOL, (ctx.tolist(), chunk, err)
+    finally:
+        c.close()

@@ -2,7 +2,8 @@
 """Benchmark of the preemptible paged-KV decode + KV reclamation path on one MI355X.
 
 One step = one pass of the whole path over one synthetic batch:
-  plan (host) -> for every layer: attention slices through the slice scheduler + merge
+  for every layer: attention slices through the slice scheduler + merge -> plan (host) and
+  upload for the next decode step, overlapping the last layers in flight
   -> reclaim the highest-address range (relocation plan, chunked block copy, table
   rewrite, hand-over) -> the online tenant returns the range and the pool bookkeeping
   is rewound so that every step does the same work (host-only, microseconds; the KV
@@ -184,10 +185,14 @@ def main():
                                             max_inflight=args.max_inflight, stream=stream)
             assert s_ == vkv.VKV_OK
 
+    vkv.kv_attn_bind(pool, ws, stream)      # the plan made above, for the first step
+
     def step():
+        decode_pass()
+        # the plan of the next decode step is made and uploaded while the last layers of this one are
+        # still running (the upload is ordered after them on the stream): one plan + bind per step
         vkv.kv_attn_plan(pool, st.ctx_len, slice_bytes, chunk_tokens)
         vkv.kv_attn_bind(pool, ws, stream)
-        decode_pass()
         rs = vkv.kv_reclaim_range(pool, lo, hi, tables, remap, chunk_bytes=rc_chunk, copy_stream=stream)
         # the online tenant gives the range back; rewind the bookkeeping for the next step
         vkv.kv_pool_return_range(pool, lo, hi)

@@ -177,3 +177,69 @@ def test_oracle_output_has_not_drifted():
     assert [[int(a), int(b)] for a, b in zip(src, dst)] == rec["reclaim"]["moves"]
     assert digest(orc.tables.astype(np.int32)) == rec["reclaim"]["tables_sha256"]
     assert digest(orc.live.astype(np.uint8)) == rec["reclaim"]["live_sha256"]
+
+
+# ------------------------------------------------------------------ MIAD and cooldown gate, stepped by hand
+def _library():
+    import paper_2604_07874_amd as vkv
+    if not os.path.exists(vkv.library_path()):
+        from paper_2604_07874_amd import build
+        build.build(verbose=False)
+    return vkv
+
+
+def test_miad_traces_oracle():
+    from oracle.policy import Miad
+    traces = load("miad_traces.json")["traces"]
+    assert len(traces) >= 2
+    for tr in traces:
+        assert len(tr["rows"]) >= 12 and len(tr["rows"]) == len(tr["why"])
+        m = Miad(**tr["config"])
+        for i, (now, used, h, grow, rel, ev, t) in enumerate(tr["rows"]):
+            assert m.observe(now, used) == (h, grow, rel, ev, t), (tr["name"], i, tr["why"][i])
+
+
+def test_miad_traces_library():
+    vkv = _library()
+    for tr in load("miad_traces.json")["traces"]:
+        m = vkv.kv_miad_init(**tr["config"])
+        try:
+            for i, (now, used, h, grow, rel, ev, t) in enumerate(tr["rows"]):
+                assert vkv.kv_miad_observe(m, now, used) == (h, grow, rel, ev, t), (tr["name"], i, tr["why"][i])
+        finally:
+            vkv.kv_miad_destroy(m)
+
+
+def _run_gate(busy, idle, poll, steps, why, name):
+    for i, (op, now, req, want) in enumerate(steps):
+        if op == "busy":
+            got = busy(now, req)
+        elif op == "idle":
+            idle(now)
+            got = 0
+        else:
+            got = poll(now)
+        assert got == want, (name, i, why[i])
+
+
+def test_cooldown_traces_oracle():
+    from oracle.policy import CooldownGate
+    traces = load("cooldown_traces.json")["traces"]
+    assert len(traces) >= 2
+    for tr in traces:
+        assert len(tr["steps"]) == len(tr["why"])
+        g = CooldownGate(tr["initial_gap_s"])
+        _run_gate(g.online_busy, g.online_idle, g.poll, tr["steps"], tr["why"], tr["name"])
+        assert g.g == tr["final"]["max_gap_s"] and g.preemptions == tr["final"]["preemptions"]
+
+
+def test_cooldown_traces_library():
+    vkv = _library()
+    for tr in load("cooldown_traces.json")["traces"]:
+        g = vkv.kv_gate_init(tr["initial_gap_s"])
+        try:
+            _run_gate(lambda t, r: vkv.kv_gate_online_busy(g, t, r), lambda t: vkv.kv_gate_online_idle(g, t),
+                      lambda t: vkv.kv_gate_poll(g, t), tr["steps"], tr["why"], tr["name"])
+            assert vkv.kv_gate_stats(g) == (tr["final"]["max_gap_s"], tr["final"]["preemptions"])
+        finally:
+            vkv.kv_gate_destroy(g)

@@ -187,6 +187,42 @@ int kv_attn_run_layer(vkv_pool* pool, int32_t layer, int32_t* cursor_slice,
                       void* workspace, void* out_f32, float softmax_scale,
                       int32_t max_inflight, void* stream);
 
+/* For callers that cannot allocate or be handed a workspace: code that is being
+ * recorded into a HIP graph, tight serving loops, harnesses that forbid hipMalloc.
+ * One whole layer of decode attention as paged_decode_attn_slice computes it, in
+ * one launch, with no plan, no bind and no workspace argument: the progress
+ * counters and the per-chunk partial results live in a 16 MiB array that is part
+ * of the library's device image (each GPU the library runs on holds its own copy
+ * until the process ends).  The call allocates nothing and frees nothing, on the
+ * device or through the runtime; it enqueues one small fill kernel (the counters
+ * must start at zero whatever an earlier call left behind) and the attention
+ * kernel on `stream`, and returns.
+ *   ctx_len_dev    device int32 [num_seqs], every value in [1, max_ctx_tokens]
+ *   max_ctx_tokens upper bound of the context lengths, <= max_blk * 16; the grid
+ *                  has one workgroup per (sequence, chunk slot, kv head), and
+ *                  workgroups past the end of their sequence exit at once
+ *   chunk_tokens   as for kv_attn_plan; for equal chunk_tokens the output bits
+ *                  equal those of the planned path
+ *   err_flag_dev   device uint32, may be NULL: bit 0 is set if a block-table
+ *                  entry outside [0, NB) was met (it is skipped), bit 1 if a
+ *                  context length was outside [1, max_ctx_tokens] (it is clamped;
+ *                  a sequence of length < 1 gets no output).  The caller clears it.
+ *   other arguments as for paged_decode_attn_slice.
+ * Limit: num_seqs * ceil(max_ctx_tokens / chunk_tokens) * kv_heads work items
+ * whose counters and partial results fit the 16 MiB (VKV_E_NOSPACE otherwise, and
+ * nothing is enqueued; the message gives the size needed).
+ * All calls on one GPU share that GPU's array: two calls whose kernels may run
+ * at the same time on one GPU (different streams, different threads) race;
+ * calls on one stream, or otherwise ordered, are fine.  The first call on a
+ * device looks the array's address up (no allocation); make that call outside
+ * graph capture.  kv_pool_init does the lookup already when given device memory.
+ * Errors: VKV_E_INVAL, VKV_E_NOSPACE, VKV_E_HIP. */
+int paged_decode_attn_layer_static(vkv_pool* pool, int32_t layer, const void* q_bf16,
+                                   const int32_t* block_table, int32_t max_blk,
+                                   const int32_t* ctx_len_dev, int32_t num_seqs, int32_t max_ctx_tokens,
+                                   int32_t chunk_tokens, void* out_f32, uint32_t* err_flag_dev,
+                                   float softmax_scale, void* stream);
+
 /* With enable != 0 the slice schedulers (kv_attn_run_layer, kv_prefill_run_layer)
  * send every other slice of a layer to a second stream owned by the pool
  * (created on first use, default priority), forked from and joined back into the

@@ -18,6 +18,7 @@ __all__ = [
     "last_error", "kv_pool_init", "kv_pool_destroy", "kv_pool_alloc", "kv_pool_adopt", "kv_pool_free",
     "kv_pool_return_range", "kv_pool_state", "kv_pool_check_tables", "kv_attn_plan", "kv_attn_plan_read",
     "kv_attn_bind", "paged_decode_attn_slice", "kv_attn_check", "kv_attn_run_layer",
+    "paged_decode_attn_layer_static",
     "kv_yield_request", "kv_yield_clear", "kv_yield_pending", "kv_reclaim_plan", "kv_reclaim_range",
     "block_table_rewrite", "kv_profile_enable", "kv_profile_read", "ProfileRecord",
     "VKV_PROF_SLICE", "VKV_PROF_RELOCATE", "VKV_PROF_REWRITE",
@@ -115,6 +116,8 @@ _sigs = {
     "kv_attn_bind": (C.c_int, [_P, _P, C.c_uint64, _P]),
     "paged_decode_attn_slice": (C.c_int, [_P, C.c_int32, C.c_int32, _P, _P, C.c_int32, _P, _P, C.c_float, _P]),
     "kv_attn_check": (C.c_int, [_P, _P, _P]),
+    "paged_decode_attn_layer_static": (C.c_int, [_P, C.c_int32, _P, _P, C.c_int32, _P, C.c_int32, C.c_int32, C.c_int32,
+                                                 _P, _P, C.c_float, _P]),
     "kv_attn_run_layer": (C.c_int, [_P, C.c_int32, _I32P, _P, _P, C.c_int32, _P, _P, C.c_float, C.c_int32, _P]),
     "kv_yield_request": (C.c_int, [_P]),
     "kv_yield_clear": (C.c_int, [_P]),
@@ -268,6 +271,13 @@ def paged_decode_attn_slice(pool, layer: int, slice_idx: int, q, block_table, wo
                             softmax_scale: float = 0.0, stream=None):
     _check(lib.paged_decode_attn_slice(pool, layer, slice_idx, _dev(q), _dev(block_table), block_table.shape[-1],
                                        _dev(workspace), _dev(out), softmax_scale, _stream(stream)))
+
+
+def paged_decode_attn_layer_static(pool, layer: int, q, block_table, ctx_len_dev, max_ctx_tokens: int,
+                                   chunk_tokens: int, out, err_flag_dev=None, softmax_scale: float = 0.0, stream=None):
+    _check(lib.paged_decode_attn_layer_static(pool, layer, _dev(q), _dev(block_table), block_table.shape[-1],
+                                              _dev(ctx_len_dev), ctx_len_dev.numel(), max_ctx_tokens, chunk_tokens,
+                                              _dev(out), _dev(err_flag_dev), softmax_scale, _stream(stream)))
 
 
 def kv_attn_check(pool, workspace, stream=None):

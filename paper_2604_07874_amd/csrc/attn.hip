@@ -12,6 +12,39 @@ namespace vkv {
 
 #include "attn_kernel.inc"
 
+// ---- scratch of the entry point that allocates nothing ---------------------------------
+// paged_decode_attn_layer_static keeps its progress counters and per-item partial results here
+// instead of in a caller-provided workspace.  Every GPU holds its own copy of the array at its
+// own address; the name below is only a host-side stand-in for it, so host code looks the
+// device address up once per device and uses that pointer everywhere.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char static_scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mu;
+static void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of static_scratch on the current device (looked up on the first call there).
+int static_scratch_for_current_device(void** out) {
+  int dev = -1;
+  VKV_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) { set_error("device ordinal %d not supported", dev); return VKV_E_INVAL; }
+  std::lock_guard<std::mutex> g(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    VKV_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(static_scratch)));
+    if (!ptr) { set_error("hipGetSymbolAddress gave no address for the static scratch"); return VKV_E_HIP; }
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return VKV_OK;
+}
+
+__global__ void zero_words_kernel(uint32_t* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+
 static int check_bound(vkv_pool* p, const void* workspace, const char* who) {
   if (!p) { set_error("%s: null pool", who); return VKV_E_INVAL; }
   if (p->broken) { set_error("%s: pool unusable after a HIP failure", who); return VKV_E_HIP; }
@@ -52,9 +85,9 @@ static int launch_slice(vkv_pool* p, int32_t layer, int32_t slice, const void* q
   a.scale_log2 = (scale != 0.f ? scale : 1.0f / std::sqrt((float)D)) * 1.4426950408889634f;
   ProfScope prof(p, VKV_PROF_SLICE, slice, st);
   if (D == 128)
-    hipLaunchKernelGGL(paged_decode_attn_slice_kernel<128>, dim3((unsigned)count), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((paged_decode_attn_slice_kernel<128, false>), dim3((unsigned)count), dim3(256), 0, st, a);
   else
-    hipLaunchKernelGGL(paged_decode_attn_slice_kernel<64>, dim3((unsigned)count), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((paged_decode_attn_slice_kernel<64, false>), dim3((unsigned)count), dim3(256), 0, st, a);
   VKV_HIP(hipGetLastError());
   return VKV_OK;
 }
@@ -346,6 +379,86 @@ int kv_attn_run_layer(vkv_pool* p, int32_t layer, int32_t* cursor, const void* q
                       return launch_slice(p, layer, s, q, table, max_blk, workspace, out, scale, on);
                     },
                     0, nullptr);
+}
+
+int paged_decode_attn_layer_static(vkv_pool* p, int32_t layer, const void* q, const int32_t* table, int32_t max_blk,
+                                   const int32_t* ctx_len_dev, int32_t num_seqs, int32_t max_ctx_tokens,
+                                   int32_t chunk_tokens, void* out, uint32_t* err_flag_dev, float scale, void* stream) {
+  const char* who = "paged_decode_attn_layer_static";
+  if (!p) { set_error("%s: null pool", who); return VKV_E_INVAL; }
+  if (p->broken) { set_error("%s: pool unusable after a HIP failure", who); return VKV_E_HIP; }
+  if (!p->cfg.base) { set_error("%s: pool has no device memory", who); return VKV_E_INVAL; }
+  if (layer < 0 || layer >= p->cfg.num_layers) { set_error("%s: layer %d out of range", who, layer); return VKV_E_INVAL; }
+  if (!q || !table || !ctx_len_dev || !out || (uintptr_t)q % 16 || (uintptr_t)err_flag_dev % 4) {
+    set_error("%s: q (16-byte aligned), block_table, ctx_len and out must be given", who);
+    return VKV_E_INVAL;
+  }
+  if (chunk_tokens < kGroupTokens || chunk_tokens % kGroupTokens || chunk_tokens > kMaxChunkTokens) {
+    set_error("%s: chunk_tokens must be a multiple of %d in [%d, %d]", who, kGroupTokens, kGroupTokens, kMaxChunkTokens);
+    return VKV_E_INVAL;
+  }
+  const int B = p->cfg.block_tokens, Hkv = p->cfg.num_kv_heads, D = p->cfg.head_dim, G = p->G;
+  if (num_seqs < 1 || max_ctx_tokens < 1 || max_blk < 1 || (int64_t)max_ctx_tokens > (int64_t)max_blk * B) {
+    set_error("%s: need num_seqs >= 1 and 1 <= max_ctx_tokens <= max_blk * %d", who, B);
+    return VKV_E_INVAL;
+  }
+  const int64_t max_chunks = ((int64_t)max_ctx_tokens + chunk_tokens - 1) / chunk_tokens;
+  if (max_chunks * G * 8 > kMergeLdsBytes) {
+    set_error("%s: %lld chunks per sequence is too many for group size %d; raise chunk_tokens", who,
+              (long long)max_chunks, G);
+    return VKV_E_INVAL;
+  }
+  const int64_t n_items = (int64_t)num_seqs * max_chunks * Hkv;
+  // scratch: [0,256) header (word 0 = flag when the caller gives none) | done | (max, sum) | weighted V sums
+  const uint64_t off_done = 256;
+  const uint64_t off_ml = align_up(off_done + (uint64_t)num_seqs * Hkv * 4, 256);
+  const uint64_t off_acc = align_up(off_ml + (uint64_t)n_items * G * 2 * 4, 256);
+  const uint64_t need = max_chunks > 1 ? off_acc + (uint64_t)n_items * G * D * 4 : off_ml;
+  if (n_items > 0x7FFFFFF0ll || need > kStaticScratchBytes) {
+    set_error("%s: %d sequences x %lld chunks x %d kv heads need %llu bytes of scratch, the static buffer holds %llu; "
+              "raise chunk_tokens, split the batch, or use paged_decode_attn_slice with a workspace",
+              who, num_seqs, (long long)max_chunks, Hkv, (unsigned long long)need,
+              (unsigned long long)kStaticScratchBytes);
+    return VKV_E_NOSPACE;
+  }
+  void* base_v = nullptr;
+  int st = static_scratch_for_current_device(&base_v);
+  if (st != VKV_OK) return st;
+  char* sc = (char*)base_v;
+  hipStream_t hs = (hipStream_t)stream;
+  // the counters (and the flag word) must start at zero whatever an earlier call left behind; a fill
+  // kernel, not a memset, so that the call can be recorded into a graph
+  const int n_zero = (int)((off_ml - 0) / 4);
+  hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)((n_zero + 255) / 256)), dim3(256), 0, hs, (uint32_t*)sc, n_zero);
+  VKV_HIP(hipGetLastError());
+  AttnParams a{};
+  a.pool = (const uint16_t*)p->cfg.base + (uint64_t)layer * ((uint64_t)2 * Hkv * 16 * D);
+  a.q = (const uint16_t*)q;
+  a.table = table;
+  a.part_acc = (float*)(sc + off_acc);
+  a.part_ml = (float*)(sc + off_ml);
+  a.done = (int32_t*)(sc + off_done);
+  a.out = (float*)out;
+  a.err = err_flag_dev ? err_flag_dev : (uint32_t*)sc;
+  a.block_elems = p->block_elems;
+  a.v_off = (uint32_t)(Hkv * 16 * D);
+  a.max_blk = max_blk;
+  a.Hq = p->cfg.num_q_heads;
+  a.Hkv = Hkv;
+  a.G = G;
+  a.NB = p->cfg.num_blocks;
+  a.chunk_blocks = chunk_tokens / B;
+  a.scale_log2 = (scale != 0.f ? scale : 1.0f / std::sqrt((float)D)) * 1.4426950408889634f;
+  a.ctx_len = ctx_len_dev;
+  a.max_chunks = (int32_t)max_chunks;
+  a.max_ctx = max_ctx_tokens;
+  ProfScope prof(p, VKV_PROF_SLICE, 0, hs);
+  if (D == 128)
+    hipLaunchKernelGGL((paged_decode_attn_slice_kernel<128, true>), dim3((unsigned)n_items), dim3(256), 0, hs, a);
+  else
+    hipLaunchKernelGGL((paged_decode_attn_slice_kernel<64, true>), dim3((unsigned)n_items), dim3(256), 0, hs, a);
+  VKV_HIP(hipGetLastError());
+  return VKV_OK;
 }
 
 int kv_sched_set_overlap(vkv_pool* p, int32_t enable) {

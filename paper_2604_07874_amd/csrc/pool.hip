@@ -108,6 +108,12 @@ int kv_pool_init(const vkv_pool_config* c, vkv_pool** out) {
   p->block_elems = be;
   p->block_bytes = be * 2;
   p->live.assign((size_t)c->num_blocks, 0);
+  if (c->base) {
+    // a pool with device memory: find this device's copy of the static scratch now, so that
+    // paged_decode_attn_layer_static has nothing left to set up (a failure here is reported there)
+    void* scratch = nullptr;
+    (void)static_scratch_for_current_device(&scratch);
+  }
   *out = p;
   return VKV_OK;
 }

@@ -167,6 +167,10 @@ struct ProfScope {
   }
 };
 
+// Device address of the library's static scratch array on the current device (attn.hip);
+// the first call on a device looks it up.
+int static_scratch_for_current_device(void** out);
+
 // Slice scheduler shared by decode and prefill (attn.hip).
 // true if handles [first, last) of the arena all have physical memory behind them
 bool arena_range_mapped(const vkv_arena* a, int32_t first, int32_t last);

@@ -125,9 +125,11 @@ typedef struct vkv_attn_plan_info {
  * consecutive items into slices reading at most slice_bytes of K+V (at least
  * one item each), so that a yield request is honoured within one slice
  * (Section 2.3, Challenge 1: bounded preemption latency).
- * ctx_len_host[s] >= 1 counts the tokens already in the cache, the newest
- * included.  chunk_tokens: multiple of 32 in [32, 2048].  Replaces any earlier plan.
- * Errors: VKV_E_INVAL. */
+ * ctx_len_host[s] >= 0 counts the tokens already in the cache, the newest
+ * included; 0 = the sequence is not in the batch (a request that was evicted
+ * and went back to the waiting state, Section 5): it gets no work and its
+ * output rows are not written.  chunk_tokens: multiple of 32 in [32, 2048].
+ * Replaces any earlier plan.  Errors: VKV_E_INVAL. */
 int kv_attn_plan(vkv_pool* pool, const int32_t* ctx_len_host, int32_t num_seqs,
                  uint64_t slice_bytes, int32_t chunk_tokens, vkv_attn_plan_info* info_out);
 

@@ -18,12 +18,6 @@ slice      = maximal run of consecutive items whose K+V bytes sum to at most
 A context length of 0 stands for a sequence that is not in the batch (a request
 that was evicted and sent back to the waiting state, Section 5, "Sub-layer
 memory reclamation"): it contributes no work.
-
-`balanced_attention_plan` is the second way of cutting the same work: instead of
-fixed-size chunks it deals every slice out in equal shares to a given number of
-queues (one per workgroup the GPU holds at once), so that all of them finish
-together.  The paper prescribes neither; both are this library's answer to its
-bounded-preemption requirement.
 """
 from __future__ import annotations
 
@@ -57,57 +51,6 @@ def attention_plan(ctx_len, num_kv_heads: int, head_dim: int, block_tokens: int,
     starts.append(len(work))
     return (np.asarray(work, dtype=np.int32).reshape(-1, 4),
             np.asarray(starts, dtype=np.int32))
-
-
-def balanced_attention_plan(ctx_len, num_kv_heads: int, head_dim: int, block_tokens: int,
-                            slice_bytes: int, slots: int, max_item_tokens: int = 2048, unit_tokens: int = 32):
-    """Equal shares instead of fixed chunks.
-
-    stream = for sequence s (ascending), for kv head h (ascending): the tokens of s in units of
-             `unit_tokens` (the last unit of a (s, h) pair may be short).
-    slice  = consecutive runs of floor(slice_bytes / bytes of one unit) units of the stream (at
-             least one unit), the last slice taking what is left.
-    queue  = a slice of u units is dealt to Q = min(slots, u) queues; queue j takes the units
-             floor(j u / Q) .. floor((j + 1) u / Q) - 1 of the slice (shares differ by at most one unit).
-    item   = a run of units of one queue inside one (s, h) pair, cut further into runs of at most
-             max_item_tokens; written (sequence, kv_head, first_block_index, n_tokens).
-    Items are listed in stream order.  Returns (work int32 [n_items, 4], slice_start int32
-    [n_slices + 1] in items, queue int32 [n_items]: number of the item's queue, counted through
-    all slices).
-    """
-    if unit_tokens % block_tokens or max_item_tokens % unit_tokens or max_item_tokens < unit_tokens or slots < 1:
-        raise ValueError("bad unit, item bound or slot count")
-    unit_bytes = unit_tokens * 2 * head_dim * 2
-    slice_units = max(1, slice_bytes // unit_bytes)
-    # the stream, one entry per unit: (sequence, head, unit index inside the pair, tokens in the unit)
-    stream = []
-    for s, n in enumerate(int(v) for v in ctx_len):
-        if n < 0:
-            raise ValueError("context length must not be negative")
-        for h in range(num_kv_heads):
-            for u in range(-(-n // unit_tokens)):
-                stream.append((s, h, u, min(unit_tokens, n - u * unit_tokens)))
-    work, queue_of, starts = [], [], [0]
-    n_queues = 0
-    for lo in range(0, len(stream), slice_units):
-        units = stream[lo:lo + slice_units]
-        u = len(units)
-        q = min(slots, u)
-        for j in range(q):
-            share = units[j * u // q:(j + 1) * u // q]
-            run = []                      # units of the item being built
-            for k, (s, h, idx, ntok) in enumerate(share):
-                run.append((s, h, idx, ntok))
-                last = k + 1 == len(share)
-                if last or share[k + 1][:2] != (s, h) or len(run) * unit_tokens == max_item_tokens:
-                    s0, h0, idx0, _ = run[0]
-                    work.append((s0, h0, idx0 * unit_tokens // block_tokens, sum(r[3] for r in run)))
-                    queue_of.append(n_queues + j)
-                    run = []
-        n_queues += q
-        starts.append(len(work))
-    return (np.asarray(work, dtype=np.int32).reshape(-1, 4), np.asarray(starts, dtype=np.int32),
-            np.asarray(queue_of, dtype=np.int32))
 
 
 def prefill_plan(ctx_len, q_len, num_q_heads: int, num_kv_heads: int, head_dim: int, block_tokens: int,

@@ -178,6 +178,14 @@ int run_slices(vkv_pool* p, int32_t* cursor, int32_t n_slices, int32_t max_infli
     }
     const hipStream_t on = (two && (s & 1)) ? p->aux_stream : hs;
     if ((st = admit()) != VKV_OK) return st;
+    // admit() may have waited for up to one slice: a request that came in meanwhile is honoured now
+    if (p->yield_flag.load(std::memory_order_acquire)) {
+      st = drain();
+      if (st != VKV_OK) return st;
+      if ((st = join()) != VKV_OK) return st;
+      *cursor = s;
+      return VKV_YIELDED;
+    }
     if ((st = launch(s, on)) != VKV_OK) return st;
     if ((st = track(on)) != VKV_OK) return st;
     if (on != hs) aux_used = true;
@@ -191,6 +199,12 @@ int run_slices(vkv_pool* p, int32_t* cursor, int32_t n_slices, int32_t max_infli
       return VKV_YIELDED;
     }
     if ((st = admit()) != VKV_OK) return st;
+    if (p->yield_flag.load(std::memory_order_acquire)) {
+      st = drain();
+      if (st != VKV_OK) return st;
+      *cursor = n_slices + t;
+      return VKV_YIELDED;
+    }
     if ((st = tail(t)) != VKV_OK) return st;
     if ((st = track(hs)) != VKV_OK) return st;
   }
@@ -216,7 +230,7 @@ int kv_attn_plan(vkv_pool* p, const int32_t* ctx, int32_t S, uint64_t slice_byte
   int64_t n_items = 0;
   int32_t max_blocks = 0;
   for (int32_t s = 0; s < S; ++s) {
-    if (ctx[s] < 1) { set_error("kv_attn_plan: sequence %d has context length %d (< 1)", s, ctx[s]); return VKV_E_INVAL; }
+    if (ctx[s] < 0) { set_error("kv_attn_plan: sequence %d has context length %d (< 0)", s, ctx[s]); return VKV_E_INVAL; }
     n_items += (int64_t)((ctx[s] + chunk_tokens - 1) / chunk_tokens) * Hkv;
     max_blocks = std::max(max_blocks, (ctx[s] + B - 1) / B);
   }
@@ -255,7 +269,7 @@ int kv_attn_plan(vkv_pool* p, const int32_t* ctx, int32_t S, uint64_t slice_byte
     total += b;
   }
   max_slice = std::max(max_slice, acc);
-  starts.push_back((int32_t)work.size());
+  if (!work.empty()) starts.push_back((int32_t)work.size());   // an empty batch has no slice
 
   // Workgroups start in grid order.  Inside a slice the longest items go first, so the short
   // ones (ragged ends of sequences) fill the tail of the launch; equal items keep the plan's

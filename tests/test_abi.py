@@ -99,7 +99,16 @@ def test_attention_plan_matches_oracle(vkv, name):
         with pytest.raises(vkv.VkvError):
             vkv.kv_attn_plan(p, st.ctx_len, 1 << 20, bad_chunk)
     with pytest.raises(vkv.VkvError):
-        vkv.kv_attn_plan(p, np.array([5, 0], dtype=np.int32), 1 << 20, 64)
+        vkv.kv_attn_plan(p, np.array([5, -1], dtype=np.int32), 1 << 20, 64)
+    # a sequence that has left the batch (length 0) gets no work
+    ctx0 = st.ctx_len.copy()
+    ctx0[0] = 0
+    info = vkv.kv_attn_plan(p, ctx0, 1 << 22, 128)
+    work, starts = vkv.kv_attn_plan_read(p, info)
+    owork, ostarts = attention_plan(ctx0, g.num_kv_heads, g.head_dim, g.block_tokens, 128, 1 << 22)
+    assert np.array_equal(work, owork) and np.array_equal(starts, ostarts) and 0 not in work[:, 0]
+    info = vkv.kv_attn_plan(p, np.zeros(3, dtype=np.int32), 1 << 22, 128)
+    assert info.n_items == 0 and info.n_slices == 0
     vkv.kv_pool_destroy(p)
 
 

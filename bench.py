@@ -2,15 +2,19 @@
 """Benchmark of the preemptible paged-KV decode + KV reclamation path on one MI355X.
 
 One step = one pass of the whole path over one synthetic batch:
-  for every layer: attention slices through the slice scheduler + merge -> plan (host) and
+  for every layer: attention slices through the slice scheduler (+ merge) -> plan (host) and
   upload for the next decode step, overlapping the last layers in flight
   -> reclaim the highest-address range (relocation plan, chunked block copy, table
-  rewrite, hand-over) -> the online tenant returns the range and the pool bookkeeping
-  is rewound so that every step does the same work (host-only, microseconds; the KV
-  bytes themselves never move back because the copy leaves the sources intact).
+  rewrite, hand-over; enqueued behind the decode on the same stream) -> the online tenant
+  returns the range and the pool bookkeeping is rewound so that every step does the same work
+  (host-only, microseconds; the KV bytes themselves never move back because the copy leaves
+  the sources intact).
 
-Prints ONE JSON line.  `value` is the algorithmic HBM bytes of a step (K+V bytes read
-by attention in all layers + bytes read and written by the relocation) divided by the
+With no --workload the run covers every timed configuration, one after the other in one
+process: the largest single-GPU one (stress, 200 GiB pool) is the headline of the JSON line and
+the others (llama8b, llama70b_tp8, offline_batch) are records of the same shape under
+"workloads".  Prints ONE JSON line.  `value` is the algorithmic HBM bytes of a step (K+V bytes
+read by attention in all layers + bytes read and written by the relocation) divided by the
 wall time of a step, inputs resident in HBM.
 """
 from __future__ import annotations
@@ -29,49 +33,73 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published
+HEADLINE = "stress"
+EVENT_STRIDE = 8         # launches per bracketed launch inside the timed steps
+ALL_WORKLOADS = ["stress", "llama8b", "llama70b_tp8", "offline_batch"]
+T_BEGIN = time.time()
 
 
-def measured_traffic_ratio(workload: str):
-    """HBM bytes / algorithmic bytes of the attention kernel from the committed counter run,
-    or None when there is none for this workload or the kernel source has changed since."""
+def progress(msg):
+    """Phase marker on stderr (stdout carries the one JSON line only)."""
+    print(f"[bench {time.time() - T_BEGIN:7.1f}s] {msg}", file=sys.stderr, flush=True)
+
+
+def measured_traffic(workload: str):
+    """(attention HBM bytes / algorithmic bytes, relocation HBM bytes / algorithmic bytes) from the
+    committed counter run of this workload; an entry is None when there is no run or the kernel's
+    source has changed since it was taken."""
     import hashlib
     path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
-    src = os.path.join(ROOT, "paper_2604_07874_amd", "csrc", "attn_kernel.inc")
-    if not (os.path.exists(path) and os.path.exists(src)):
-        return None
-    kv = dict(l.split(":", 1) for l in open(path) if l.startswith("attn_"))
-    if kv.get("attn_source_sha256", "").strip() != hashlib.sha256(open(src, "rb").read()).hexdigest():
-        return None
-    return float(kv["attn_traffic_ratio"])
+    if not os.path.exists(path):
+        return None, None
+    kv = dict(l.split(":", 1) for l in open(path) if l.startswith(("attn_", "reloc_")))
+
+    def sha(rel):
+        return hashlib.sha256(open(os.path.join(ROOT, "paper_2604_07874_amd", "csrc", rel), "rb").read()).hexdigest()
+
+    attn = reloc = None
+    try:
+        if kv.get("attn_source_sha256", "").strip() == sha("attn_kernel.inc"):
+            attn = float(kv["attn_traffic_ratio"])
+        if kv.get("reloc_source_sha256", "").strip() == sha("reclaim.hip"):
+            reloc = float(kv["reloc_traffic_ratio"])
+    except (KeyError, ValueError, OSError):
+        pass
+    return attn, reloc
 
 
 def percentile(a, q):
     return float(np.percentile(np.asarray(a, dtype=np.float64), q)) if len(a) else None
 
 
-def main():
+def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="llama8b")
+    ap.add_argument("--workload", default="all",
+                    help="one of the configurations, or 'all': the headline one and then the others as sub-records")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--chunk-tokens", type=int, default=None)
     ap.add_argument("--slice-bytes", type=int, default=None)
     ap.add_argument("--reclaim-chunk-bytes", type=int, default=None)
     ap.add_argument("--max-inflight", type=int, default=2)
-    ap.add_argument("--yield-injections", type=int, default=1000)
-    ap.add_argument("--concurrent-reclaim", action="store_true",
-                    help="extra leg: rate-capped, chunked reclamation on a second stream while decode runs")
+    ap.add_argument("--yield-injections", type=int, default=300)
+    ap.add_argument("--concurrent-reclaim", dest="concurrent_reclaim", action="store_true", default=None,
+                    help="extra leg: rate-capped, chunked reclamation on a second stream while decode runs "
+                         "(default: on for workloads that define a rate cap)")
+    ap.add_argument("--no-concurrent-reclaim", dest="concurrent_reclaim", action="store_false")
     ap.add_argument("--rate-cap", type=float, default=None, help="bytes/s for the concurrent leg")
-    ap.add_argument("--overlap-slices", action="store_true",
-                    help="alternate the slices of a layer between two streams (kv_sched_set_overlap)")
+    ap.add_argument("--overlap-slices", dest="overlap", action="store_true", default=None,
+                    help="alternate the slices of a layer between two streams (default: on when a layer has more "
+                         "than one slice)")
+    ap.add_argument("--no-overlap-slices", dest="overlap", action="store_false")
     ap.add_argument("--arena", action="store_true",
                     help="pool memory from a handle-backed arena; the burst leg then unmaps the handed-over range "
                          "(physical memory back to the driver) and maps it again when the range is returned")
-    ap.add_argument("--bursts", type=int, default=0,
+    ap.add_argument("--bursts", type=int, default=None,
                     help="extra leg: this many online bursts (yield, reclaim, hold, return) at exponential "
-                         "inter-arrival times while decode runs continuously")
+                         "inter-arrival times while decode runs continuously (default: 25 for the stress workload)")
     ap.add_argument("--burst-mean-s", type=float, default=0.2)
     ap.add_argument("--burst-hold-ms", type=float, default=20.0)
     ap.add_argument("--prefill-leg", dest="prefill_leg", action="store_true", default=None,
@@ -82,16 +110,19 @@ def main():
     ap.add_argument("--prefill-slice-bytes", type=int, default=512 << 20)
     ap.add_argument("--prefill-one-stream", action="store_true",
                     help="prefill leg without overlapped slices (then per-launch durations are additive)")
-    ap.add_argument("--prefill-yield-injections", type=int, default=200)
+    ap.add_argument("--prefill-yield-injections", type=int, default=100)
     ap.add_argument("--prefill-chunk-tokens", type=int, default=4096)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-baseline-layers", type=int, default=6,
-                    help="layers of the whole batch the oracle is timed on (about 2 s of one core each at the 8B shape)")
+    ap.add_argument("--cpu-baseline-bytes", type=float, default=1.5e9,
+                    help="K+V bytes of the sample the oracle is timed on, per workload (about 2.5 s of one core per GB)")
     ap.add_argument("--cpu-workers", type=int, default=min(16, os.cpu_count() or 1),
                     help="worker processes for the all-cores timing of the oracle (0 = skip it)")
-    ap.add_argument("--no-launch-events", action="store_true",
-                    help="do not bracket launches with timing events (roofline fields become null)")
-    args = ap.parse_args()
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the bandwidth yardsticks")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
     if args.gpus != 1:
         print("bench.py: this library runs on one GPU only (no sharding, no collectives); use --gpus 1",
               file=sys.stderr)
@@ -110,29 +141,64 @@ def main():
             workers = None
 
     import torch
-    import synth
-    import paper_2604_07874_amd as vkv
-
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    torch.cuda.set_device(torch.device("cuda:0"))
+
+    names = ALL_WORKLOADS if args.workload == "all" else [args.workload]
+    records = {}
+    for name in names:
+        progress(f"==== workload {name} ====")
+        try:
+            records[name] = run_workload(name, args, workers)
+        except Exception as e:      # one configuration failing must not take the others' figures with it
+            if name == names[0]:
+                raise
+            records[name] = {"error": f"{type(e).__name__}: {e}"}
+        import gc
+        gc.collect()
+        torch.cuda.empty_cache()
+    if workers is not None:
+        workers.close()
+        workers.join()
+
+    head = records[names[0]]
+    line = {
+        "metric": "reclaim GB/s & paged-decode GB/s (% HBM peak); p99 yield latency us",
+        "value": head["value"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+    }
+    line.update({k: v for k, v in head.items() if k not in line})
+    if len(names) > 1:
+        line["workloads"] = {n: records[n] for n in names[1:]}
+        line["summary"] = {n: {k: records[n].get(k) for k in
+                               ("value", "frac_of_hbm_peak", "decode_GBps", "decode_frac_of_peak", "reclaim_traffic_GBps",
+                                "reclaim_frac_of_peak", "yield_latency_us_p99")}
+                           | {"attn_kernel_frac": (records[n].get("roofline") or {}).get("frac"),
+                              "relocate_kernel_frac": (records[n].get("roofline_reclaim") or {}).get("frac")}
+                           for n in names if "error" not in records[n]}
+    print(json.dumps(line), flush=True)
+
+
+def run_workload(name, args, workers):
+    """Everything for one configuration: inputs, timed steps, per-kernel figures, legs, oracle timing.
+    Returns the record (the fields of the JSON line that belong to one workload)."""
+    import torch
+    import synth
+    import paper_2604_07874_amd as vkv
+
     dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-
-    t_begin_run = time.time()
-
-    def progress(msg):
-        """Phase marker on stderr (stdout carries the one JSON line only)."""
-        print(f"[bench {time.time() - t_begin_run:7.1f}s] {msg}", file=sys.stderr, flush=True)
-
-    wl = synth.workload(args.workload)
+    wl = synth.workload(name)
     g = wl.geom
-    if args.prefill_leg is None:
-        args.prefill_leg = wl.name == "llama8b"
     chunk_tokens = args.chunk_tokens or wl.chunk_tokens
     slice_bytes = args.slice_bytes or wl.slice_bytes
     rc_chunk = wl.chunk_bytes if args.reclaim_chunk_bytes is None else args.reclaim_chunk_bytes
     L, S = g.num_layers, wl.num_seqs
+    prefill_leg = (wl.name == "llama8b") if args.prefill_leg is None else args.prefill_leg
+    concurrent_leg = (wl.rate_cap > 0) if args.concurrent_reclaim is None else args.concurrent_reclaim
+    n_bursts = (25 if wl.name == "stress" else 0) if args.bursts is None else args.bursts
 
     # ---- inputs, resident in HBM before anything is timed --------------------------
     t_setup = time.time()
@@ -145,7 +211,7 @@ def main():
     else:
         pool_t = torch.empty(g.pool_elems, dtype=torch.int16, device=dev)
     progress(f"filling the {g.pool_bytes / 2**30:.0f} GiB pool on the device")
-    fill_step = 1 << 33                                   # elements per progress line (16 GiB)
+    fill_step = 1 << 34                                   # elements per progress line (32 GiB)
     for lo_e in range(0, g.pool_elems, fill_step):
         hi_e = min(g.pool_elems, lo_e + fill_step)
         synth.fill_pool_range_torch(pool_t, g, args.seed, lo_e, hi_e)
@@ -162,9 +228,9 @@ def main():
     vkv.kv_pool_adopt(pool, np.flatnonzero(st.live).astype(np.int32))
     if arena is not None:
         vkv.kv_pool_attach_arena(pool, arena)
-    if args.overlap_slices:
-        vkv.kv_sched_set_overlap(pool, True)
     info = vkv.kv_attn_plan(pool, st.ctx_len, slice_bytes, chunk_tokens)
+    overlap = (info.n_slices > 1) if args.overlap is None else bool(args.overlap)
+    vkv.kv_sched_set_overlap(pool, overlap)
     ws = torch.empty(info.workspace_bytes, dtype=torch.uint8, device=dev)
     lo, hi = wl.reclaim_range
     remap_plan, plan_stats = vkv.kv_reclaim_plan(pool, lo, hi, g.num_blocks)
@@ -174,16 +240,29 @@ def main():
     setup_s = time.time() - t_setup
 
     stream = torch.cuda.current_stream()
-    launches_per_step = L * info.n_slices + 2 + (len(src_ids) // max(1, rc_chunk // g.block_bytes) + 1 if rc_chunk else 1)
-    use_events = not args.no_launch_events
-    if use_events:
+    reclaim_launches = (len(src_ids) // max(1, rc_chunk // g.block_bytes) + 1) if rc_chunk else 1
+    launches_per_step = L * info.n_slices + 2 + reclaim_launches
+    # launches overlapped on two streams have durations that are not additive: they are timed in a
+    # one-stream pass of their own after the timed steps
+    events_in_steps = not overlap
+    if events_in_steps:
+        # every eighth launch is bracketed: two event records around a launch cost its neighbours several
+        # microseconds, and the timed steps should run as an untimed caller's would
         vkv.kv_profile_enable(pool, launches_per_step * (args.steps + 1) + 16)
+        vkv.kv_profile_sample(pool, EVENT_STRIDE)
 
     def decode_pass():
         for layer in range(L):
             s_, cur = vkv.kv_attn_run_layer(pool, layer, 0, q_all[layer], tables, ws, out[layer],
                                             max_inflight=args.max_inflight, stream=stream)
             assert s_ == vkv.VKV_OK
+
+    def rewind():
+        # the online tenant gives the range back; rewind the bookkeeping so that every step does the same work
+        vkv.kv_pool_return_range(pool, lo, hi)
+        vkv.kv_pool_free(pool, dst_ids)
+        vkv.kv_pool_adopt(pool, src_ids)
+        tables.copy_(tables0, non_blocking=True)
 
     vkv.kv_attn_bind(pool, ws, stream)      # the plan made above, for the first step
 
@@ -193,19 +272,19 @@ def main():
         # still running (the upload is ordered after them on the stream): one plan + bind per step
         vkv.kv_attn_plan(pool, st.ctx_len, slice_bytes, chunk_tokens)
         vkv.kv_attn_bind(pool, ws, stream)
-        rs = vkv.kv_reclaim_range(pool, lo, hi, tables, remap, chunk_bytes=rc_chunk, copy_stream=stream)
-        # the online tenant gives the range back; rewind the bookkeeping for the next step
-        vkv.kv_pool_return_range(pool, lo, hi)
-        vkv.kv_pool_free(pool, dst_ids)
-        vkv.kv_pool_adopt(pool, src_ids)
-        tables.copy_(tables0, non_blocking=True)
+        # the reclamation is enqueued behind the decode on the same stream, so every slice has finished
+        # before the first block moves and nothing has to be waited for on the host: the next step's
+        # slices are ordered behind the copy and the table rewrite in turn
+        rs = vkv.kv_reclaim_range(pool, lo, hi, tables, remap, chunk_bytes=rc_chunk, copy_stream=stream,
+                                  flags=vkv.VKV_RECLAIM_ASYNC)
+        rewind()
         return rs
 
     progress("inputs resident; warm-up steps")
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    if use_events:
+    if events_in_steps:
         vkv.kv_profile_read(pool, 1 << 20)   # drop warm-up records
 
     progress("timed steps")
@@ -223,91 +302,105 @@ def main():
     step_bytes = decode_bytes + reclaim_traffic
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
 
-    # ---- per-kernel figures from the events recorded inside the timed region -------
-    roofline = None
-    roofline_reclaim = None
-    extra = {}
-    if use_events:
-        rec = vkv.kv_profile_read(pool, 1 << 20)
-        sl = rec[rec["kind"] == vkv.VKV_PROF_SLICE]
-        rl = rec[rec["kind"] == vkv.VKV_PROF_RELOCATE]
-        rw = rec[rec["kind"] == vkv.VKV_PROF_REWRITE]
-        n_slice_launches = len(sl)
-        slice_ms_avg = float(sl["ms"].mean())
-        bytes_per_launch = decode_bytes_layer / info.n_slices
-        ach = bytes_per_launch / (slice_ms_avg * 1e-3) / 1e9
-        ratio = measured_traffic_ratio(wl.name)
-        roofline = {"kernel": "paged_decode_attn_slice_kernel", "bound": "hbm", "achieved": round(ach, 1),
-                    "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4),
-                    "traffic": None if ratio is None else int(ratio * bytes_per_launch), "avg_launch_us": round(slice_ms_avg * 1e3, 2),
-                    "bytes_per_launch": int(bytes_per_launch), "launches": int(n_slice_launches)}
-        if len(rl) and int(rl["index"].sum()) > 0:
-            n_launches = int(rl["index"].sum())
-            rl_ms = float(rl["ms"].sum())                    # all copy launches, gaps between them included
-            per_launch_ms = rl_ms / n_launches
-            per_launch_bytes = reclaim_traffic * len(rl) / n_launches
-            rach = per_launch_bytes / (per_launch_ms * 1e-3) / 1e9
-            roofline_reclaim = {"kernel": "kv_block_relocate_kernel", "bound": "hbm", "achieved": round(rach, 1),
-                                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(rach / HBM_PEAK_GBPS, 4),
-                                "traffic": None, "avg_launch_us": round(per_launch_ms * 1e3, 2),
-                                "bytes_per_launch": int(per_launch_bytes), "launches": n_launches}
-        extra.update({
-            "slice_us_p50": round(percentile(sl["ms"], 50) * 1e3, 1),
-            "slice_us_p99": round(percentile(sl["ms"], 99) * 1e3, 1),
-            "slice_us_max": round(float(sl["ms"].max()) * 1e3, 1),
-            "rewrite_us_avg": round(float(rw["ms"].mean()) * 1e3, 2) if len(rw) else None,
-        })
-        vkv.kv_profile_enable(pool, 0)
-
-    progress("bandwidth yardsticks")
-    # ---- yardsticks: what the memory system gives a sequential read and the runtime's own copy
-    def timed_ms(fn, reps):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        fn(0)
+    # ---- per-kernel figures from events recorded around every launch on its stream ----------
+    if not events_in_steps:
+        progress("one-stream pass with launch events (kernel durations)")
+        vkv.kv_sched_set_overlap(pool, False)
+        vkv.kv_profile_enable(pool, 2 * launches_per_step + 16)
+        vkv.kv_profile_sample(pool, 3)
+        decode_pass()
+        vkv.kv_reclaim_range(pool, lo, hi, tables, remap, chunk_bytes=rc_chunk, copy_stream=stream)
+        rewind()
         torch.cuda.synchronize()
-        e0.record(stream)
-        for i in range(reps):
-            fn(i + 1)
-        e1.record(stream)
-        e1.synchronize()
-        return e0.elapsed_time(e1) / reps
-
-    pool_bytes = g.pool_elems * 2
-    sink = torch.zeros(256, dtype=torch.uint8, device=dev)
-    big = min(pool_bytes, 8 << 30) // 65536 * 65536
-    launch_sized = int(decode_bytes_layer / info.n_slices) // 65536 * 65536
-    n_regions = max(1, pool_bytes // launch_sized)
-    base_addr = pool_t.data_ptr()
-    read_big_ms = timed_ms(lambda i: vkv.kv_probe_read(base_addr, big, sink, stream), 4)
-    read_launch_ms = timed_ms(lambda i: vkv.kv_probe_read(base_addr + (i % n_regions) * launch_sized, launch_sized,
-                                                          sink, stream), 16)
-    # the attention kernel's own reads without its arithmetic: slices of all layers in turn
-    n_probe = L * info.n_slices
-    probe_ms = timed_ms(lambda i: [vkv.kv_probe_attn_reads(pool, (i * 7 + l) % L, sl, tables, ws, sink, stream)
-                                   for l in range(L) for sl in range(info.n_slices)], 2) / n_probe
-    cp_bytes = 1 << 30
-    cp_a = torch.empty(cp_bytes, dtype=torch.uint8, device=dev)
-    cp_b = torch.empty(cp_bytes, dtype=torch.uint8, device=dev)
-    copy_ms = timed_ms(lambda i: vkv.kv_probe_copy(cp_b, cp_a, cp_bytes, stream), 4)
-    del cp_a, cp_b
-    ceilings = {
-        "sequential_read_GBps": round(big / read_big_ms / 1e6, 1), "sequential_read_bytes": int(big),
-        "sequential_read_at_launch_size_GBps": round(launch_sized / read_launch_ms / 1e6, 1),
-        "launch_size_bytes": int(launch_sized),
-        "attention_reads_only_GBps": round(decode_bytes_layer / info.n_slices / probe_ms / 1e6, 1),
-        "runtime_copy_traffic_GBps": round(2 * cp_bytes / copy_ms / 1e6, 1), "copy_bytes": cp_bytes,
+    rec = vkv.kv_profile_read(pool, 1 << 20)
+    vkv.kv_profile_enable(pool, 0)
+    vkv.kv_sched_set_overlap(pool, overlap)
+    sl = rec[rec["kind"] == vkv.VKV_PROF_SLICE]
+    rl = rec[rec["kind"] == vkv.VKV_PROF_RELOCATE]
+    rw = rec[rec["kind"] == vkv.VKV_PROF_REWRITE]
+    slice_ms_avg = float(sl["ms"].mean())
+    bytes_per_launch = decode_bytes_layer / info.n_slices
+    ach = bytes_per_launch / (slice_ms_avg * 1e-3) / 1e9
+    attn_ratio, reloc_ratio = measured_traffic(wl.name)
+    roofline = {"kernel": "paged_decode_attn_slice_kernel", "bound": "hbm", "achieved": round(ach, 1),
+                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4),
+                "traffic": None if attn_ratio is None else int(attn_ratio * bytes_per_launch),
+                "avg_launch_us": round(slice_ms_avg * 1e3, 2),
+                "bytes_per_launch": int(bytes_per_launch), "launches": int(len(sl)),
+                "method": (f"HIP events around every {EVENT_STRIDE}th launch inside the timed steps" if events_in_steps else
+                           "HIP events around every 3rd launch in a one-stream pass after the timed steps (the timed "
+                           "steps alternate slices between two streams, where durations are not additive)")}
+    roofline_reclaim = None
+    if len(rl) and int(rl["index"].sum()) > 0:
+        n_launches = int(rl["index"].sum())
+        rl_ms = float(rl["ms"].sum())                    # all copy launches, gaps between them included
+        per_launch_ms = rl_ms / n_launches
+        per_launch_bytes = reclaim_traffic * len(rl) / n_launches
+        rach = per_launch_bytes / (per_launch_ms * 1e-3) / 1e9
+        roofline_reclaim = {"kernel": "kv_block_relocate_kernel", "bound": "hbm", "achieved": round(rach, 1),
+                            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(rach / HBM_PEAK_GBPS, 4),
+                            "traffic": None if reloc_ratio is None else int(reloc_ratio * per_launch_bytes),
+                            "avg_launch_us": round(per_launch_ms * 1e3, 2),
+                            "bytes_per_launch": int(per_launch_bytes), "launches": n_launches}
+    extra = {
+        "slice_us_p50": round(percentile(sl["ms"], 50) * 1e3, 1),
+        "slice_us_p99": round(percentile(sl["ms"], 99) * 1e3, 1),
+        "slice_us_max": round(float(sl["ms"].max()) * 1e3, 1),
+        "rewrite_us_avg": round(float(rw["ms"].mean()) * 1e3, 2) if len(rw) else None,
     }
-    if roofline is not None:
+
+    # ---- yardsticks: what the memory system gives a sequential read and the runtime's own copy
+    ceilings = None
+    if not args.no_ceilings:
+        progress("bandwidth yardsticks")
+
+        def timed_ms(fn, reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            fn(0)
+            torch.cuda.synchronize()
+            e0.record(stream)
+            for i in range(reps):
+                fn(i + 1)
+            e1.record(stream)
+            e1.synchronize()
+            return e0.elapsed_time(e1) / reps
+
+        pool_bytes = g.pool_elems * 2
+        sink = torch.zeros(256, dtype=torch.uint8, device=dev)
+        big = min(pool_bytes, 8 << 30) // 65536 * 65536
+        launch_sized = int(bytes_per_launch) // 65536 * 65536
+        n_regions = max(1, pool_bytes // launch_sized)
+        base_addr = pool_t.data_ptr()
+        read_big_ms = timed_ms(lambda i: vkv.kv_probe_read(base_addr, big, sink, stream), 4)
+        read_launch_ms = timed_ms(lambda i: vkv.kv_probe_read(base_addr + (i % n_regions) * launch_sized, launch_sized,
+                                                              sink, stream), 16)
+        # the attention kernel's own reads without its arithmetic: slices of (up to 4) layers in turn
+        probe_layers = min(L, 4)
+        n_probe = probe_layers * info.n_slices
+        probe_ms = timed_ms(lambda i: [vkv.kv_probe_attn_reads(pool, (i * 3 + l) % L, s_, tables, ws, sink, stream)
+                                       for l in range(probe_layers) for s_ in range(info.n_slices)], 2) / n_probe
+        cp_bytes = 1 << 30
+        cp_a = torch.empty(cp_bytes, dtype=torch.uint8, device=dev)
+        cp_b = torch.empty(cp_bytes, dtype=torch.uint8, device=dev)
+        copy_ms = timed_ms(lambda i: vkv.kv_probe_copy(cp_b, cp_a, cp_bytes, stream), 4)
+        del cp_a, cp_b
+        ceilings = {
+            "sequential_read_GBps": round(big / read_big_ms / 1e6, 1), "sequential_read_bytes": int(big),
+            "sequential_read_at_launch_size_GBps": round(launch_sized / read_launch_ms / 1e6, 1),
+            "launch_size_bytes": int(launch_sized),
+            "attention_reads_only_GBps": round(bytes_per_launch / probe_ms / 1e6, 1),
+            "runtime_copy_traffic_GBps": round(2 * cp_bytes / copy_ms / 1e6, 1), "copy_bytes": cp_bytes,
+        }
         roofline["frac_of_read_ceiling_at_launch_size"] = round(
             roofline["achieved"] / ceilings["sequential_read_at_launch_size_GBps"], 4)
         roofline["frac_of_own_reads_only"] = round(roofline["achieved"] / ceilings["attention_reads_only_GBps"], 4)
-    if roofline_reclaim is not None:
-        roofline_reclaim["frac_of_runtime_copy"] = round(
-            roofline_reclaim["achieved"] / ceilings["runtime_copy_traffic_GBps"], 4)
+        if roofline_reclaim is not None:
+            roofline_reclaim["frac_of_runtime_copy"] = round(
+                roofline_reclaim["achieved"] / ceilings["runtime_copy_traffic_GBps"], 4)
 
     progress("decode-only and reclaim-only legs")
     # ---- separate legs: decode only, reclaim only (wall clock, no launch events) ----
-    reps = max(3, args.steps)
+    reps = max(3, min(args.steps, 10))
     decode_pass()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -321,20 +414,9 @@ def main():
         t0 = time.perf_counter()
         vkv.kv_reclaim_range(pool, lo, hi, tables, remap, chunk_bytes=rc_chunk, copy_stream=stream)
         reclaim_ms.append((time.perf_counter() - t0) * 1e3)
-        vkv.kv_pool_return_range(pool, lo, hi)
-        vkv.kv_pool_free(pool, dst_ids)
-        vkv.kv_pool_adopt(pool, src_ids)
-        tables.copy_(tables0)
+        rewind()
+    torch.cuda.synchronize()
     reclaim_ms_med = float(np.median(reclaim_ms))
-    if roofline is not None and args.overlap_slices and info.n_slices > 1:
-        # launches of one layer overlap on two streams, so per-launch durations are not additive:
-        # rate the kernel by the wall clock of the decode-only leg instead (launch gaps included)
-        ach = decode_bytes / (decode_ms * 1e-3) / 1e9
-        roofline.update({"achieved": round(ach, 1), "frac": round(ach / HBM_PEAK_GBPS, 4),
-                         "avg_launch_us": round(decode_ms * 1e3 / (L * info.n_slices), 2),
-                         "method": "wall clock of the decode-only leg / launches (overlapped launches)",
-                         "frac_of_read_ceiling_at_launch_size": round(
-                             ach / ceilings["sequential_read_at_launch_size_GBps"], 4)})
     extra.update({
         "decode_GBps": round(decode_bytes / (decode_ms * 1e-3) / 1e9, 1),
         "decode_frac_of_peak": round(decode_bytes / (decode_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
@@ -347,9 +429,9 @@ def main():
         "reclaim_blocks_moved": int(rs.blocks_moved),
     })
 
-    progress("yield injections")
     # ---- end-to-end yield latency: request at a random instant, until compute is off the GPU
     if args.yield_injections > 0:
+        progress("yield injections")
         rng = np.random.default_rng(args.seed)
         lat = []
         req_t = [0.0]
@@ -359,15 +441,14 @@ def main():
             req_t[0] = time.perf_counter()
             vkv.kv_yield_request(pool)
 
-        n_inj = args.yield_injections
         layer = 0
         cur = 0
-        budget_s = 60.0
+        budget_s = 20.0
         t_begin = time.time()
-        for i in range(n_inj):
+        for i in range(args.yield_injections):
             if time.time() - t_begin > budget_s:
                 break
-            delay = float(rng.uniform(0.0, decode_ms * 1e-3))
+            delay = float(rng.uniform(0.0, min(decode_ms, 10.0) * 1e-3))
             th = threading.Thread(target=requester, args=(delay,))
             th.start()
             landed = None
@@ -383,13 +464,15 @@ def main():
             lat.append((landed - req_t[0]) * 1e6)
             vkv.kv_yield_clear(pool)
         torch.cuda.synchronize()
+        # finish the layer the last injection interrupted (a started layer must be finished or rebound)
+        vkv.kv_attn_bind(pool, ws, stream)
         extra.update({"yield_latency_us_p50": round(percentile(lat, 50), 1),
                       "yield_latency_us_p99": round(percentile(lat, 99), 1),
                       "yield_latency_us_max": round(max(lat), 1), "yield_injections": len(lat)})
 
-    progress("optional legs")
     # ---- optional: reclamation under a rate cap on a second stream while decode keeps running
-    if args.concurrent_reclaim:
+    if concurrent_leg:
+        progress("concurrent rate-capped reclamation leg")
         cap = args.rate_cap or wl.rate_cap or 20e9
         cchunk = rc_chunk or (64 << 20)
         decode_stream, copy_stream = torch.cuda.Stream(), torch.cuda.Stream()
@@ -420,252 +503,53 @@ def main():
         stop.set()
         th.join()
         torch.cuda.synchronize()
-        vkv.kv_pool_return_range(pool, lo, hi)
-        vkv.kv_pool_free(pool, dst_ids)
-        vkv.kv_pool_adopt(pool, src_ids)
-        tables.copy_(tables0)
+        rewind()
+        torch.cuda.synchronize()
         extra.update({
             "concurrent_rate_cap_GBps": cap / 1e9,
             "concurrent_reclaim_achieved_GBps": round(crs.bytes_moved / crs.host_seconds / 1e9, 2),
             "concurrent_reclaim_ms": round(crs.host_seconds * 1e3, 2),
             "concurrent_reclaim_launches": int(crs.n_chunks),
             "concurrent_decode_GBps": round((n_b - n_a) * decode_bytes_layer / (t_b - t_a) / 1e9, 1),
+            "concurrent_decode_frac_of_peak": round((n_b - n_a) * decode_bytes_layer / (t_b - t_a) / 1e9 / HBM_PEAK_GBPS, 4),
         })
 
     # ---- optional: online bursts against a continuous offline decode loop --------------------
-    # Each burst: yield request -> offline compute off the GPU -> the top range emptied and handed
-    # over -> the online tenant holds it -> range returned, offline resumes (its KV "grows back":
-    # the bookkeeping is rewound; the sources were left intact by the copy).
-    if args.bursts > 0:
-        brng = np.random.default_rng(args.seed + 1)
-        arrivals = np.cumsum(brng.exponential(args.burst_mean_s, size=args.bursts))
-        decode_stream, copy_stream = torch.cuda.Stream(), torch.cuda.Stream()
-        torch.cuda.synchronize()
-        stop = threading.Event()
-        cv = threading.Condition()
-        gate = {"want_pause": False, "paused": False}    # both only change under cv
-        layers_done = [0]
-
-        def offline():
-            layer, cur = 0, 0
-            while not stop.is_set():
-                with cv:
-                    while gate["want_pause"] and not stop.is_set():
-                        gate["paused"] = True          # nothing of ours is on the GPU: every call below
-                        cv.notify_all()                # returns only after its launches have drained
-                        cv.wait(0.05)
-                    gate["paused"] = False
-                s_, cur = vkv.kv_attn_run_layer(pool, layer, cur, q_all[layer], tables, ws, out[layer],
-                                                max_inflight=args.max_inflight, stream=decode_stream)
-                if s_ != vkv.VKV_YIELDED:
-                    layers_done[0] += 1
-                    layer, cur = (layer + 1) % L, 0
-            decode_stream.synchronize()
-
-        blocks_v = pool_t.view(g.num_blocks, g.block_elems)
-        src_dev = torch.from_numpy(src_ids).to(dev).long()
-        dst_dev = torch.from_numpy(dst_ids).to(dev).long()
-        unmap_ms, map_ms = [], []
-
-        def give_back(unmapped=False):
-            if unmapped:
-                t_m = time.perf_counter()
-                vkv.kv_arena_restore(arena, pool, lo, hi)
-                map_ms.append((time.perf_counter() - t_m) * 1e3)
-            vkv.kv_pool_return_range(pool, lo, hi)
-            vkv.kv_pool_free(pool, dst_ids)
-            vkv.kv_pool_adopt(pool, src_ids)
-            if unmapped:
-                # the range came back with fresh memory: the offline tenant's blocks move back in
-                with torch.cuda.stream(copy_stream):
-                    for i in range(0, len(src_ids), 1024):
-                        blocks_v[src_dev[i:i + 1024]] = blocks_v[dst_dev[i:i + 1024]]
-            with torch.cuda.stream(copy_stream):
-                tables.copy_(tables0)
-            copy_stream.synchronize()
-
-        # one untimed reclamation on the two new streams (their first use creates queues)
-        progress("burst leg: untimed reclamation on the new streams")
-        vkv.kv_reclaim_range(pool, lo, hi, tables, remap, chunk_bytes=rc_chunk, copy_stream=copy_stream,
-                             decode_stream=decode_stream)
-        give_back()
-        progress("burst leg: offline loop starts")
-        th = threading.Thread(target=offline)
-        t_start = time.perf_counter()
-        th.start()
-        to_idle, to_released, paused = [], [], 0.0
-        for a in arrivals:
-            now = time.perf_counter() - t_start
-            if a > now:
-                time.sleep(a - now)
-            t_arr = max(a, now) + t_start     # a burst that finds the previous one in service waits its turn
-            t_req = time.perf_counter()
-            verbose = len(to_released) < 3
-            if verbose:
-                progress(f"  burst {len(to_released)}: yield requested after {layers_done[0]} layers")
-            with cv:
-                gate["want_pause"] = True
-            vkv.kv_yield_request(pool)
-            with cv:
-                while not gate["paused"]:
-                    cv.wait()
-            t_idle = time.perf_counter()
-            if verbose:
-                progress("    offline compute is off the GPU; reclaiming")
-            vkv.kv_reclaim_range(pool, lo, hi, tables, remap, chunk_bytes=rc_chunk, copy_stream=copy_stream,
-                                 decode_stream=decode_stream)
-            t_rel = time.perf_counter()      # handed over: a tenant in this process may use the range now
-            if arena is not None:
-                vkv.kv_arena_release(arena, pool, lo, hi)     # the physical memory is the driver's again
-                unmap_ms.append((time.perf_counter() - t_rel) * 1e3)
-            to_idle.append((t_idle - t_req) * 1e3)
-            to_released.append((t_rel - min(t_arr, t_req)) * 1e3)
-            if verbose:
-                progress("    range handed over; online tenant holds it")
-            time.sleep(args.burst_hold_ms * 1e-3)
-            give_back(unmapped=arena is not None)
-            vkv.kv_yield_clear(pool)
-            paused += time.perf_counter() - t_req
-            with cv:
-                gate["want_pause"] = False
-                cv.notify_all()
-            if len(to_released) % 20 == 0:
-                progress(f"  burst {len(to_released)} of {args.bursts}")
-        stop.set()
-        th.join()
-        torch.cuda.synchronize()
-        total_s = time.perf_counter() - t_start
-        extra.update({
-            "bursts": int(args.bursts), "burst_mean_interarrival_s": args.burst_mean_s,
-            "burst_hold_ms": args.burst_hold_ms, "burst_run_s": round(total_s, 2),
-            "burst_reclaimed_bytes": int((hi - lo) * g.block_bytes), "burst_moved_bytes": int(rs.bytes_moved),
-            "burst_yield_to_idle_ms_p50": round(percentile(to_idle, 50), 3),
-            "burst_yield_to_idle_ms_p99": round(percentile(to_idle, 99), 3),
-            "burst_arrival_to_released_ms_p50": round(percentile(to_released, 50), 3),
-            "burst_arrival_to_released_ms_p99": round(percentile(to_released, 99), 3),
-            "burst_arrival_to_released_ms_max": round(max(to_released), 3),
-            "burst_offline_paused_frac": round(paused / total_s, 4),
-            "burst_decode_GBps_whole_run": round(layers_done[0] * decode_bytes_layer / total_s / 1e9, 1),
-            "burst_decode_GBps_while_running": round(layers_done[0] * decode_bytes_layer / (total_s - paused) / 1e9, 1),
-        })
-        if arena is not None:
-            extra.update({"burst_unmap_ms_p50": round(percentile(unmap_ms, 50), 3),
-                          "burst_unmap_ms_p99": round(percentile(unmap_ms, 99), 3),
-                          "burst_map_ms_p50": round(percentile(map_ms, 50), 3),
-                          "burst_map_ms_p99": round(percentile(map_ms, 99), 3)})
+    if n_bursts > 0:
+        extra.update(burst_leg(vkv, args, wl, pool, pool_t, arena, st, q_all, tables, tables0, ws, out, remap, lo, hi,
+                               rc_chunk, src_ids, dst_ids, decode_bytes_layer, int(rs.bytes_moved), n_bursts))
 
     # ---- optional: preemptible causal prefill over the same pool (MFMA-bound) -------------
-    if args.prefill_leg:
+    if prefill_leg:
         progress("prefill leg")
         try:
-            q_len = np.minimum(st.ctx_len, args.prefill_tokens).astype(np.int32)
-            pinfo = vkv.kv_prefill_plan(pool, st.ctx_len, q_len, args.prefill_slice_bytes, args.prefill_chunk_tokens)
-            pws = torch.empty(pinfo.workspace_bytes, dtype=torch.uint8, device=dev)
-            vkv.kv_prefill_bind(pool, pws, stream)
-            pq = torch.empty((pinfo.total_q, g.num_q_heads, g.head_dim), dtype=torch.int16, device=dev)
-            # query values: the generator's bits at the start of the pool serve as well as any
-            pq.view(-1).copy_(pool_t[:pq.numel()])
-            pout = torch.empty((pinfo.total_q, g.num_q_heads, g.head_dim), dtype=torch.float32, device=dev)
-            p_overlap = not args.prefill_one_stream
-            vkv.kv_sched_set_overlap(pool, p_overlap)
-            vkv.kv_profile_enable(pool, (pinfo.n_slices + pinfo.n_merge_steps) * 3 + 16)
-            n_layers_p = min(L, 2)
-            for layer in range(n_layers_p):           # warm-up
-                vkv.kv_prefill_run_layer(pool, layer, 0, pq, tables, pws, pout, max_inflight=args.max_inflight, stream=stream)
-            torch.cuda.synchronize()
-            vkv.kv_profile_read(pool, 1 << 20)
-            t0 = time.perf_counter()
-            for layer in range(n_layers_p):
-                vkv.kv_prefill_run_layer(pool, layer, 0, pq, tables, pws, pout, max_inflight=args.max_inflight, stream=stream)
-            torch.cuda.synchronize()
-            dt = (time.perf_counter() - t0) / n_layers_p
-            rec = vkv.kv_profile_read(pool, 1 << 20)
-            psl = rec[rec["kind"] == vkv.VKV_PROF_PREFILL]
-            pmg = rec[rec["kind"] == vkv.VKV_PROF_PREFILL_MERGE]
-            vkv.kv_profile_enable(pool, 0)
-            # overlapped launches: per-launch durations are not additive, rate by the wall clock instead
-            kern_s = dt if p_overlap else float(psl["ms"].sum()) * 1e-3 / n_layers_p
-            extra.update({
-                "prefill_rows": int(pinfo.total_q), "prefill_slices_per_layer": int(pinfo.n_slices),
-                "prefill_items_per_layer": int(pinfo.n_items), "prefill_merge_steps_per_layer": int(pinfo.n_merge_steps),
-                "prefill_overlapped_slices": p_overlap,
-                "prefill_slice_bytes": args.prefill_slice_bytes, "prefill_chunk_tokens": args.prefill_chunk_tokens,
-                "prefill_TFLOPs_wall": round(pinfo.flops_per_layer / dt / 1e12, 1),
-                "prefill_TFLOPs_kernel": None if p_overlap else round(pinfo.flops_per_layer / kern_s / 1e12, 1),
-                "prefill_frac_of_mfma_bf16_peak": round(pinfo.flops_per_layer / kern_s / 2.5e15, 4),
-                "prefill_ms_per_layer": round(dt * 1e3, 3),
-                "prefill_slice_us_p50": round(percentile(psl["ms"], 50) * 1e3, 1),
-                "prefill_slice_us_p99": round(percentile(psl["ms"], 99) * 1e3, 1),
-                "prefill_kv_GBps": round(pinfo.kv_bytes_per_layer / kern_s / 1e9, 1),
-                "prefill_merge_us_per_layer": round(float(pmg["ms"].sum()) * 1e3 / n_layers_p, 1),
-                "prefill_merge_step_us_max": round(float(pmg["ms"].max()) * 1e3, 1) if len(pmg) else None,
-            })
-            # yield latency of a prefill: request at a random instant of a layer, until compute is off the GPU
-            if args.prefill_yield_injections > 0:
-                prng = np.random.default_rng(args.seed + 2)
-                plat, preq = [], [0.0]
-
-                def prequester(delay):
-                    time.sleep(delay)
-                    preq[0] = time.perf_counter()
-                    vkv.kv_yield_request(pool)
-
-                layer, cur, t_begin = 0, 0, time.time()
-                for _ in range(args.prefill_yield_injections):
-                    if time.time() - t_begin > 40.0:
-                        break
-                    th = threading.Thread(target=prequester, args=(float(prng.uniform(0.0, dt)),))
-                    th.start()
-                    landed = None
-                    while landed is None:
-                        s_, cur = vkv.kv_prefill_run_layer(pool, layer, cur, pq, tables, pws, pout,
-                                                           max_inflight=args.max_inflight, stream=stream)
-                        if s_ == vkv.VKV_YIELDED:
-                            landed = time.perf_counter()
-                        else:
-                            layer, cur = (layer + 1) % n_layers_p, 0
-                    th.join()
-                    plat.append((landed - preq[0]) * 1e6)
-                    vkv.kv_yield_clear(pool)
-                torch.cuda.synchronize()
-                extra.update({"prefill_yield_latency_us_p50": round(percentile(plat, 50), 1),
-                              "prefill_yield_latency_us_p99": round(percentile(plat, 99), 1),
-                              "prefill_yield_latency_us_max": round(max(plat), 1), "prefill_yield_injections": len(plat)})
-            vkv.kv_prefill_check(pool, pws, stream)
-            vkv.kv_sched_set_overlap(pool, bool(args.overlap_slices))
-            del pws, pq, pout
+            extra.update(prefill_leg_run(vkv, args, wl, pool, pool_t, st, tables, stream, overlap))
         except Exception as e:      # an extra leg must not take the headline line down with it
             extra["prefill_error"] = f"{type(e).__name__}: {e}"
             vkv.kv_yield_clear(pool)
 
-    progress("CPU oracle baseline")
     # ---- the CPU oracle on a bounded sample of the same workload --------------------
     cpu_baseline = None
     if not args.no_cpu_baseline:
+        progress("CPU oracle baseline")
         try:
             cpu_baseline = cpu_oracle_baseline(wl, st, pool_t, q_all, decode_bytes, reclaim_traffic,
-                                               args.cpu_baseline_layers, workers, args.cpu_workers, progress)
+                                               args.cpu_baseline_bytes, workers, args.cpu_workers)
         except Exception as e:      # the GPU figures above stand on their own
             cpu_baseline = {"error": f"{type(e).__name__}: {e}", "kind": "oracle"}
-    if workers is not None:
-        workers.close()
-        workers.join()
 
     vkv.kv_pool_destroy(pool)
     if arena is not None:
         del pool_t
         vkv.kv_arena_destroy(arena)
-    line = {
-        "metric": "reclaim GB/s & paged-decode GB/s (% HBM peak); p99 yield latency us",
-        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+    record = {
+        "value": round(value, 1), "unit": "GB/s", "ms_per_step": round(ms_per_step, 4),
         "config": {"workload": (f"{wl.name}: L={L} Hq={g.num_q_heads} Hkv={g.num_kv_heads} D={g.head_dim} "
                                 f"block={g.block_tokens} batch={S} ctx={wl.ctx_dist} pool={g.pool_bytes / 2**30:.1f}GiB "
                                 f"occupancy={wl.occupancy} reclaim_top={(hi - lo) * g.block_bytes / 2**30:.2f}GiB"),
                    "chunk_tokens": chunk_tokens, "slice_bytes": slice_bytes, "n_slices_per_layer": info.n_slices,
                    "n_items_per_layer": info.n_items, "reclaim_chunk_bytes": rc_chunk,
-                   "max_inflight": args.max_inflight, "overlap_slices": bool(args.overlap_slices),
+                   "max_inflight": args.max_inflight, "overlap_slices": bool(overlap),
                    "arena": bool(args.arena), "seed": args.seed},
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
         "step_bytes": step_bytes, "decode_bytes": decode_bytes, "reclaim_traffic_bytes": reclaim_traffic,
@@ -673,8 +557,216 @@ def main():
         "roofline": roofline, "roofline_reclaim": roofline_reclaim, "cpu_baseline": cpu_baseline,
         "ceilings": ceilings,
     }
-    line.update(extra)
-    print(json.dumps(line), flush=True)
+    record.update(extra)
+    return record
+
+
+def burst_leg(vkv, args, wl, pool, pool_t, arena, st, q_all, tables, tables0, ws, out, remap, lo, hi, rc_chunk,
+              src_ids, dst_ids, decode_bytes_layer, moved_bytes, n_bursts):
+    """Online bursts against a continuous offline decode loop.  Each burst: yield request -> offline
+    compute off the GPU -> the top range emptied and handed over -> the online tenant holds it ->
+    range returned, offline resumes (its KV "grows back": the bookkeeping is rewound; the sources
+    were left intact by the copy)."""
+    import torch
+    g = wl.geom
+    L = g.num_layers
+    dev = pool_t.device
+    progress(f"burst leg: {n_bursts} bursts")
+    brng = np.random.default_rng(args.seed + 1)
+    arrivals = np.cumsum(brng.exponential(args.burst_mean_s, size=n_bursts))
+    decode_stream, copy_stream = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    stop = threading.Event()
+    cv = threading.Condition()
+    gate = {"want_pause": False, "paused": False}    # both only change under cv
+    layers_done = [0]
+
+    def offline():
+        layer, cur = 0, 0
+        while not stop.is_set():
+            with cv:
+                while gate["want_pause"] and not stop.is_set():
+                    gate["paused"] = True          # nothing of ours is on the GPU: every call below
+                    cv.notify_all()                # returns only after its launches have drained
+                    cv.wait(0.05)
+                gate["paused"] = False
+            s_, cur = vkv.kv_attn_run_layer(pool, layer, cur, q_all[layer], tables, ws, out[layer],
+                                            max_inflight=args.max_inflight, stream=decode_stream)
+            if s_ != vkv.VKV_YIELDED:
+                layers_done[0] += 1
+                layer, cur = (layer + 1) % L, 0
+        decode_stream.synchronize()
+
+    blocks_v = pool_t.view(g.num_blocks, g.block_elems)
+    src_dev = torch.from_numpy(src_ids).to(dev).long()
+    dst_dev = torch.from_numpy(dst_ids).to(dev).long()
+    unmap_ms, map_ms = [], []
+
+    def give_back(unmapped=False):
+        if unmapped:
+            t_m = time.perf_counter()
+            vkv.kv_arena_restore(arena, pool, lo, hi)
+            map_ms.append((time.perf_counter() - t_m) * 1e3)
+        vkv.kv_pool_return_range(pool, lo, hi)
+        vkv.kv_pool_free(pool, dst_ids)
+        vkv.kv_pool_adopt(pool, src_ids)
+        if unmapped:
+            # the range came back with fresh memory: the offline tenant's blocks move back in
+            with torch.cuda.stream(copy_stream):
+                for i in range(0, len(src_ids), 1024):
+                    blocks_v[src_dev[i:i + 1024]] = blocks_v[dst_dev[i:i + 1024]]
+        with torch.cuda.stream(copy_stream):
+            tables.copy_(tables0)
+        copy_stream.synchronize()
+
+    # one untimed reclamation on the two new streams (their first use creates queues)
+    vkv.kv_reclaim_range(pool, lo, hi, tables, remap, chunk_bytes=rc_chunk, copy_stream=copy_stream,
+                         decode_stream=decode_stream)
+    give_back()
+    th = threading.Thread(target=offline)
+    t_start = time.perf_counter()
+    th.start()
+    to_idle, to_released, paused = [], [], 0.0
+    for a in arrivals:
+        now = time.perf_counter() - t_start
+        if a > now:
+            time.sleep(a - now)
+        t_arr = max(a, now) + t_start     # a burst that finds the previous one in service waits its turn
+        t_req = time.perf_counter()
+        with cv:
+            gate["want_pause"] = True
+        vkv.kv_yield_request(pool)
+        with cv:
+            while not gate["paused"]:
+                cv.wait()
+        t_idle = time.perf_counter()
+        vkv.kv_reclaim_range(pool, lo, hi, tables, remap, chunk_bytes=rc_chunk, copy_stream=copy_stream,
+                             decode_stream=decode_stream)
+        t_rel = time.perf_counter()      # handed over: a tenant in this process may use the range now
+        if arena is not None:
+            vkv.kv_arena_release(arena, pool, lo, hi)     # the physical memory is the driver's again
+            unmap_ms.append((time.perf_counter() - t_rel) * 1e3)
+        to_idle.append((t_idle - t_req) * 1e3)
+        to_released.append((t_rel - min(t_arr, t_req)) * 1e3)
+        time.sleep(args.burst_hold_ms * 1e-3)
+        give_back(unmapped=arena is not None)
+        vkv.kv_yield_clear(pool)
+        paused += time.perf_counter() - t_req
+        with cv:
+            gate["want_pause"] = False
+            cv.notify_all()
+        if len(to_released) % 10 == 0:
+            progress(f"  burst {len(to_released)} of {n_bursts}")
+    stop.set()
+    th.join()
+    torch.cuda.synchronize()
+    vkv.kv_attn_bind(pool, ws, torch.cuda.current_stream())     # the loop may have stopped inside a layer
+    torch.cuda.synchronize()
+    total_s = time.perf_counter() - t_start
+    res = {
+        "bursts": int(n_bursts), "burst_mean_interarrival_s": args.burst_mean_s,
+        "burst_hold_ms": args.burst_hold_ms, "burst_run_s": round(total_s, 2),
+        "burst_reclaimed_bytes": int((hi - lo) * g.block_bytes), "burst_moved_bytes": int(moved_bytes),
+        "burst_yield_to_idle_ms_p50": round(percentile(to_idle, 50), 3),
+        "burst_yield_to_idle_ms_p99": round(percentile(to_idle, 99), 3),
+        "burst_arrival_to_released_ms_p50": round(percentile(to_released, 50), 3),
+        "burst_arrival_to_released_ms_p99": round(percentile(to_released, 99), 3),
+        "burst_arrival_to_released_ms_max": round(max(to_released), 3),
+        "burst_offline_paused_frac": round(paused / total_s, 4),
+        "burst_decode_GBps_whole_run": round(layers_done[0] * decode_bytes_layer / total_s / 1e9, 1),
+        "burst_decode_GBps_while_running": round(layers_done[0] * decode_bytes_layer / (total_s - paused) / 1e9, 1),
+    }
+    if arena is not None:
+        res.update({"burst_unmap_ms_p50": round(percentile(unmap_ms, 50), 3),
+                    "burst_unmap_ms_p99": round(percentile(unmap_ms, 99), 3),
+                    "burst_map_ms_p50": round(percentile(map_ms, 50), 3),
+                    "burst_map_ms_p99": round(percentile(map_ms, 99), 3)})
+    return res
+
+
+def prefill_leg_run(vkv, args, wl, pool, pool_t, st, tables, stream, decode_overlap):
+    """Preemptible causal prefill of the newest tokens of every sequence over the same pool."""
+    import torch
+    g = wl.geom
+    L = g.num_layers
+    dev = pool_t.device
+    res = {}
+    q_len = np.minimum(st.ctx_len, args.prefill_tokens).astype(np.int32)
+    pinfo = vkv.kv_prefill_plan(pool, st.ctx_len, q_len, args.prefill_slice_bytes, args.prefill_chunk_tokens)
+    pws = torch.empty(pinfo.workspace_bytes, dtype=torch.uint8, device=dev)
+    vkv.kv_prefill_bind(pool, pws, stream)
+    pq = torch.empty((pinfo.total_q, g.num_q_heads, g.head_dim), dtype=torch.int16, device=dev)
+    # query values: the generator's bits at the start of the pool serve as well as any
+    pq.view(-1).copy_(pool_t[:pq.numel()])
+    pout = torch.empty((pinfo.total_q, g.num_q_heads, g.head_dim), dtype=torch.float32, device=dev)
+    p_overlap = not args.prefill_one_stream
+    vkv.kv_sched_set_overlap(pool, p_overlap)
+    vkv.kv_profile_enable(pool, (pinfo.n_slices + pinfo.n_merge_steps) * 3 + 16)
+    n_layers_p = min(L, 2)
+    for layer in range(n_layers_p):           # warm-up
+        vkv.kv_prefill_run_layer(pool, layer, 0, pq, tables, pws, pout, max_inflight=args.max_inflight, stream=stream)
+    torch.cuda.synchronize()
+    vkv.kv_profile_read(pool, 1 << 20)
+    t0 = time.perf_counter()
+    for layer in range(n_layers_p):
+        vkv.kv_prefill_run_layer(pool, layer, 0, pq, tables, pws, pout, max_inflight=args.max_inflight, stream=stream)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / n_layers_p
+    rec = vkv.kv_profile_read(pool, 1 << 20)
+    psl = rec[rec["kind"] == vkv.VKV_PROF_PREFILL]
+    pmg = rec[rec["kind"] == vkv.VKV_PROF_PREFILL_MERGE]
+    vkv.kv_profile_enable(pool, 0)
+    # overlapped launches: per-launch durations are not additive, rate by the wall clock instead
+    kern_s = dt if p_overlap else float(psl["ms"].sum()) * 1e-3 / n_layers_p
+    res.update({
+        "prefill_rows": int(pinfo.total_q), "prefill_slices_per_layer": int(pinfo.n_slices),
+        "prefill_items_per_layer": int(pinfo.n_items), "prefill_merge_steps_per_layer": int(pinfo.n_merge_steps),
+        "prefill_overlapped_slices": p_overlap,
+        "prefill_slice_bytes": args.prefill_slice_bytes, "prefill_chunk_tokens": args.prefill_chunk_tokens,
+        "prefill_TFLOPs_wall": round(pinfo.flops_per_layer / dt / 1e12, 1),
+        "prefill_TFLOPs_kernel": None if p_overlap else round(pinfo.flops_per_layer / kern_s / 1e12, 1),
+        "prefill_frac_of_mfma_bf16_peak": round(pinfo.flops_per_layer / kern_s / 2.5e15, 4),
+        "prefill_ms_per_layer": round(dt * 1e3, 3),
+        "prefill_slice_us_p50": round(percentile(psl["ms"], 50) * 1e3, 1),
+        "prefill_slice_us_p99": round(percentile(psl["ms"], 99) * 1e3, 1),
+        "prefill_kv_GBps": round(pinfo.kv_bytes_per_layer / kern_s / 1e9, 1),
+        "prefill_merge_us_per_layer": round(float(pmg["ms"].sum()) * 1e3 / n_layers_p, 1),
+        "prefill_merge_step_us_max": round(float(pmg["ms"].max()) * 1e3, 1) if len(pmg) else None,
+    })
+    # yield latency of a prefill: request at a random instant of a layer, until compute is off the GPU
+    if args.prefill_yield_injections > 0:
+        prng = np.random.default_rng(args.seed + 2)
+        plat, preq = [], [0.0]
+
+        def prequester(delay):
+            time.sleep(delay)
+            preq[0] = time.perf_counter()
+            vkv.kv_yield_request(pool)
+
+        layer, cur, t_begin = 0, 0, time.time()
+        for _ in range(args.prefill_yield_injections):
+            if time.time() - t_begin > 20.0:
+                break
+            th = threading.Thread(target=prequester, args=(float(prng.uniform(0.0, dt)),))
+            th.start()
+            landed = None
+            while landed is None:
+                s_, cur = vkv.kv_prefill_run_layer(pool, layer, cur, pq, tables, pws, pout,
+                                                   max_inflight=args.max_inflight, stream=stream)
+                if s_ == vkv.VKV_YIELDED:
+                    landed = time.perf_counter()
+                else:
+                    layer, cur = (layer + 1) % n_layers_p, 0
+            th.join()
+            plat.append((landed - preq[0]) * 1e6)
+            vkv.kv_yield_clear(pool)
+        torch.cuda.synchronize()
+        res.update({"prefill_yield_latency_us_p50": round(percentile(plat, 50), 1),
+                    "prefill_yield_latency_us_p99": round(percentile(plat, 99), 1),
+                    "prefill_yield_latency_us_max": round(max(plat), 1), "prefill_yield_injections": len(plat)})
+    vkv.kv_prefill_check(pool, pws, stream)
+    vkv.kv_sched_set_overlap(pool, bool(decode_overlap))
+    return res
 
 
 def _oracle_worker_init():
@@ -701,9 +793,10 @@ def _oracle_worker_task(task):
     return seq
 
 
-def cpu_oracle_baseline(wl, st, pool_t, q_all, decode_bytes, reclaim_traffic, n_layers, workers, n_workers, progress):
-    """Times the oracle as it stands on a sample (the whole batch, the first n_layers layers, plus a
-    reclamation of a 1024-block pool) with one thread, and again over worker processes, and scales
+def cpu_oracle_baseline(wl, st, pool_t, q_all, decode_bytes, reclaim_traffic, sample_bytes, workers, n_workers):
+    """Times the oracle as it stands on a bounded sample of this workload (the first sequences of the
+    batch, as many as give about sample_bytes of K+V per layer, over as many layers as that takes; plus
+    a reclamation of a 1024-block pool) with one thread, and again over worker processes, and scales
     both to one step's byte mix."""
     import contextlib
     import tempfile
@@ -715,9 +808,13 @@ def cpu_oracle_baseline(wl, st, pool_t, q_all, decode_bytes, reclaim_traffic, n_
     except Exception:   # pragma: no cover
         threadpool_limits = None
     g = wl.geom
-    n_layers = max(1, min(n_layers, g.num_layers))
-    n_seq = wl.num_seqs
-    # compact one-layer pools holding only the batch's blocks (ids renumbered; the attention result
+    # sample: sequences 0..n_seq-1 (all of them if one layer of the batch is below the byte target), layers 0..n_layers-1
+    per_seq_layer = st.ctx_len[:wl.num_seqs].astype(np.int64) * g.kv_bytes_per_token_layer
+    cum = np.cumsum(per_seq_layer)
+    n_seq = int(min(wl.num_seqs, max(2, np.searchsorted(cum, sample_bytes) + 1)))
+    layer_bytes = int(cum[n_seq - 1])
+    n_layers = int(max(1, min(g.num_layers, round(sample_bytes / layer_bytes))))
+    # compact one-layer pools holding only the sample's blocks (ids renumbered; the attention result
     # does not depend on block ids)
     rows = st.tables[:n_seq]
     ids = np.unique(rows[rows >= 0])
@@ -728,7 +825,7 @@ def cpu_oracle_baseline(wl, st, pool_t, q_all, decode_bytes, reclaim_traffic, n_
     sample_tables = np.where(rows >= 0, renum[np.maximum(rows, 0)], -1).astype(np.int32)
     lay = PoolLayout(1, g.num_kv_heads, g.head_dim, g.block_tokens)
     ctx = st.ctx_len[:n_seq]
-    attn_bytes = int(ctx.sum()) * g.kv_bytes_per_token_layer * n_layers
+    attn_bytes = int(ctx.astype(np.int64).sum()) * g.kv_bytes_per_token_layer * n_layers
     tmpdir = tempfile.mkdtemp(prefix="vkv_bench_", dir="/dev/shm" if os.path.isdir("/dev/shm") else None)
     files = []
     t_attn = 0.0
@@ -750,8 +847,8 @@ def cpu_oracle_baseline(wl, st, pool_t, q_all, decode_bytes, reclaim_traffic, n_
                 t0 = time.perf_counter()
                 paged_decode_attention(sample_pool, lay, q, sample_tables, ctx, 0)
                 t_attn += time.perf_counter() - t0
-                progress(f"  oracle, one thread: layer {layer} done ({t_attn:.1f} s so far)")
                 del sample_pool, blocks
+            progress(f"  oracle, one thread: {n_layers} layer(s) of {n_seq} sequences in {t_attn:.1f} s")
             # reclamation: the top 1024 blocks of the pool as a pool of their own, upper quarter reclaimed
             nb_s = min(1024, g.num_blocks) // g.blocks_per_handle * g.blocks_per_handle
             base = g.num_blocks - nb_s
@@ -773,7 +870,7 @@ def cpu_oracle_baseline(wl, st, pool_t, q_all, decode_bytes, reclaim_traffic, n_
         step_s = decode_bytes / attn_rate + (reclaim_traffic / rec_rate if rec_bytes else 0.0)
         result = {"value": round((decode_bytes + reclaim_traffic) / step_s / 1e9, 4), "unit": "GB/s", "cores": 1,
                   "kind": "oracle",
-                  "sample": (f"attention: layers 0..{n_layers - 1} of all {n_seq} sequences ({attn_bytes / 1e6:.0f} MB of "
+                  "sample": (f"attention: layers 0..{n_layers - 1} of sequences 0..{n_seq - 1} ({attn_bytes / 1e6:.0f} MB of "
                              f"K+V, {t_attn:.1f} s); reclamation: top {nb_s} blocks as a pool, {len(src)} blocks moved "
                              f"({rec_bytes / 1e6:.0f} MB read+written, {t_rec:.2f} s); scaled to one step's byte mix"),
                   "attention_GBps": round(attn_rate / 1e9, 4), "reclaim_GBps": round(rec_rate / 1e9, 3)}

@@ -175,7 +175,10 @@ int kv_attn_check(vkv_pool* pool, void* workspace, void* stream);
 /* Slice scheduler.  Issues slices *cursor_slice .. n_slices-1 of `layer`,
  * keeping at most max_inflight (1..8) launches unfinished so that the
  * host stays close to the device; the count carries over from one call to the
- * next (use one stream per pool for these calls).  Before each slice it tests
+ * next (use one stream per pool for these calls).  With max_inflight >= 2 and
+ * all slices on one stream the launches report their start through pinned host
+ * memory that the host polls, so kernels follow each other directly; otherwise
+ * an event is recorded behind every launch.  Before each slice it tests
  * the yield flag; if set it stops issuing, waits until the launches already
  * enqueued have finished, stores the next slice in *cursor_slice and returns
  * VKV_YIELDED: offline compute is then off the GPU, at most max_inflight
@@ -458,6 +461,12 @@ typedef struct vkv_profile_record {
  * 0 turns recording off and frees the events.  Used for roofline measurement;
  * the events cost a few microseconds per launch. */
 int kv_profile_enable(vkv_pool* pool, int32_t max_records);
+
+/* Brackets only every stride-th slice launch (default 1 = every launch; copy and
+ * rewrite launches are always bracketed): the two events
+ * around a launch keep its neighbours from following it directly, so sampling
+ * keeps a timed run close to an untimed one.  Errors: VKV_E_INVAL. */
+int kv_profile_sample(vkv_pool* pool, int32_t stride);
 
 /* Waits for the recorded launches to finish, writes up to cap records (launch
  * order) to out_host, their count to *n_out, and restarts recording at zero. */

@@ -20,7 +20,7 @@ __all__ = [
     "kv_attn_bind", "paged_decode_attn_slice", "kv_attn_check", "kv_attn_run_layer",
     "paged_decode_attn_layer_static",
     "kv_yield_request", "kv_yield_clear", "kv_yield_pending", "kv_reclaim_plan", "kv_reclaim_range",
-    "block_table_rewrite", "kv_profile_enable", "kv_profile_read", "ProfileRecord",
+    "block_table_rewrite", "kv_profile_enable", "kv_profile_read", "kv_profile_sample", "ProfileRecord",
     "VKV_PROF_SLICE", "VKV_PROF_RELOCATE", "VKV_PROF_REWRITE",
     "PrefillPlanInfo", "kv_prefill_plan", "kv_prefill_plan_read", "kv_prefill_bind", "paged_prefill_attn_slice",
     "kv_prefill_merge", "kv_prefill_run_layer", "kv_prefill_check", "VKV_PROF_PREFILL", "VKV_PROF_PREFILL_MERGE",
@@ -146,6 +146,7 @@ _sigs = {
     "kv_gate_stats": (C.c_int, [_P, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
     "kv_profile_enable": (C.c_int, [_P, C.c_int32]),
     "kv_profile_read": (C.c_int, [_P, _P, C.c_int32, _I32P]),
+    "kv_profile_sample": (C.c_int, [_P, C.c_int32]),
     "kv_sched_set_overlap": (C.c_int, [_P, C.c_int32]),
     "kv_arena_create": (C.c_int, [C.c_int32, C.c_uint64, C.c_int32, C.POINTER(_P), C.POINTER(_P)]),
     "kv_arena_destroy": (C.c_int, [_P]),
@@ -334,6 +335,10 @@ def block_table_rewrite(block_tables, remap_dev, num_blocks: int, stream=None):
 # ---- per-launch timing ------------------------------------------------------------
 def kv_profile_enable(pool, max_records: int):
     _check(lib.kv_profile_enable(pool, max_records))
+
+
+def kv_profile_sample(pool, stride: int):
+    _check(lib.kv_profile_sample(pool, stride))
 
 
 def kv_profile_read(pool, cap: int) -> np.ndarray:

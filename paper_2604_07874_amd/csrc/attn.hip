@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstring>
 #include <functional>
+#include <thread>
 
 namespace vkv {
 
@@ -61,7 +62,7 @@ static int launch_slice(vkv_pool* p, int32_t layer, int32_t slice, const void* q
   const int32_t first = p->slice_start[slice], count = p->slice_start[slice + 1] - first;
   const int D = p->cfg.head_dim;
   char* ws = (char*)workspace;
-  AttnParams a;
+  AttnParams a{};   // every field the launch does not set is zero (no progress report, no dense grid)
   const uint64_t layer_elems = (uint64_t)2 * p->cfg.num_kv_heads * 16 * D;
   a.pool = (const uint16_t*)p->cfg.base + (uint64_t)layer * layer_elems;
   a.work = (const WorkItem*)(ws + p->ws.work);
@@ -83,6 +84,10 @@ static int launch_slice(vkv_pool* p, int32_t layer, int32_t slice, const void* q
   a.G = p->G;
   a.NB = p->cfg.num_blocks;
   a.scale_log2 = (scale != 0.f ? scale : 1.0f / std::sqrt((float)D)) * 1.4426950408889634f;
+  if (p->report_seq) {   // the scheduler counts this launch
+    a.started = p->progress_dev;
+    a.seq = p->report_seq;
+  }
   ProfScope prof(p, VKV_PROF_SLICE, slice, st);
   if (D == 128)
     hipLaunchKernelGGL((paged_decode_attn_slice_kernel<128, false>), dim3((unsigned)count), dim3(256), 0, st, a);
@@ -109,37 +114,103 @@ static int check_slice_args(vkv_pool* p, int32_t layer, const void* q, const int
   return VKV_OK;
 }
 
+__global__ void progress_marker_kernel(uint32_t* word, uint32_t value) {
+  __hip_atomic_store(word, value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+int ensure_progress_words(vkv_pool* p) {
+  if (p->progress_host) return VKV_OK;
+  void* h = nullptr;
+  VKV_HIP(hipHostMalloc(&h, 256, hipHostMallocDefault));
+  std::memset(h, 0, 256);
+  void* d = nullptr;
+  hipError_t e = hipHostGetDevicePointer(&d, h, 0);
+  if (e != hipSuccess) { (void)hipHostFree(h); return hip_fail(e, "hipHostGetDevicePointer"); }
+  p->progress_host = (volatile uint32_t*)h;
+  p->progress_dev = (uint32_t*)d;
+  return VKV_OK;
+}
+
+// waits (polling pinned host memory; no runtime call) until *word has reached `want`
+static void wait_progress(const volatile uint32_t* word, uint32_t want) {
+  for (int spins = 0; (int32_t)(__atomic_load_n(word, __ATOMIC_ACQUIRE) - want) < 0; ++spins) {
+    if (spins < 4096) __builtin_ia32_pause();
+    else std::this_thread::sleep_for(std::chrono::microseconds(2));
+  }
+}
+
 // Slice scheduler shared by decode and prefill: issues steps *cursor .. n_slices + n_tail - 1
 // (slices through `launch`, then n_tail follow-up steps through `tail`, all on the caller's
-// stream), keeping at most max_inflight launches unfinished; the ring of events persists across
-// calls.  Stops at a step boundary when the yield flag is set.
+// stream), keeping at most max_inflight launches unfinished; that state persists across calls.
+// Stops at a step boundary when the yield flag is set.
+// How the lead over the GPU is bounded:
+//   - event ring: an event is recorded behind every launch and the host waits for the event of the
+//     launch max_inflight back.  An event record between two kernels costs several microseconds of
+//     GPU time, which does not matter when launches overlap on two streams and is used there, for
+//     steps whose kernels do not report progress (launches_report false), and for max_inflight 1.
+//   - progress words: every launch stores its number in pinned host memory when it starts, i.e. when
+//     all earlier launches of the stream have finished, and the host enqueues launch n once launch
+//     n - max_inflight + 1 has started; kernels follow each other with nothing in between.  A drain
+//     enqueues a one-thread marker kernel behind the last launch and polls for it.
 // With overlap on, odd slices go to a second stream the pool owns (forked from and joined back
 // into the caller's stream inside this call), so the workgroups of the next slice fill the
 // compute units the tail of the previous one leaves idle; slices of one layer are independent
 // (results are merged through per-item partials), so their order does not matter.
 int run_slices(vkv_pool* p, int32_t* cursor, int32_t n_slices, int32_t max_inflight, hipStream_t hs,
                const char* who, const std::function<int(int32_t, hipStream_t)>& launch, int32_t n_tail,
-               const std::function<int(int32_t)>& tail) {
+               const std::function<int(int32_t)>& tail, bool launches_report) {
   if (!cursor || *cursor < 0 || *cursor > n_slices + n_tail || max_inflight < 1 || max_inflight > kMaxInflight) {
     set_error("%s: bad cursor or max_inflight", who);
     return VKV_E_INVAL;
   }
   int st = VKV_OK;
-  for (int i = 0; i < max_inflight; ++i)
-    if (!p->inflight_ev[i]) VKV_HIP(hipEventCreateWithFlags(&p->inflight_ev[i], hipEventDisableTiming));
-  auto drain = [&]() -> int {
+  const bool two = p->overlap && p->aux_stream && max_inflight >= 2 && n_slices - *cursor >= 2;
+  const bool words = launches_report && !two && max_inflight >= 2 && n_tail == 0;
+  const int mode = words ? 2 : 1;
+
+  auto drain_ring = [&]() -> int {
     for (; p->inflight_count > 0; --p->inflight_count, p->inflight_head = (p->inflight_head + 1) % p->inflight_cap)
       VKV_HIP(hipEventSynchronize(p->inflight_ev[p->inflight_head]));
     p->inflight_head = 0;
     return VKV_OK;
   };
-  if (p->inflight_cap != max_inflight) {
-    st = drain();
-    if (st != VKV_OK) return st;
+  auto drain_words = [&]() -> int {
+    // a marker behind everything enqueued so far; it runs when the last launch has finished
+    const uint32_t mark = ++p->drain_seq;
+    hipLaunchKernelGGL(progress_marker_kernel, dim3(1), dim3(1), 0, hs, p->progress_dev + 1, mark);
+    VKV_HIP(hipGetLastError());
+    wait_progress(p->progress_host + 1, mark);
+    // the slices are done; the marker itself is about to retire: the stream is idle a moment later
+    for (;;) {
+      const hipError_t q = hipStreamQuery(hs);
+      if (q == hipSuccess) break;
+      if (q != hipErrorNotReady) return hip_fail(q, "hipStreamQuery");
+      __builtin_ia32_pause();
+    }
+    return VKV_OK;
+  };
+  auto drain = [&]() -> int { return p->sched_mode == 2 ? drain_words() : drain_ring(); };
+
+  if (mode == 2 && (st = ensure_progress_words(p)) != VKV_OK) return st;
+  if (mode == 1)
+    for (int i = 0; i < max_inflight; ++i)
+      if (!p->inflight_ev[i]) VKV_HIP(hipEventCreateWithFlags(&p->inflight_ev[i], hipEventDisableTiming));
+  if (p->sched_mode != mode || (mode == 1 && p->inflight_cap != max_inflight)) {
+    // another way of counting from here on: nothing of the old way may be left in flight
+    if (p->sched_mode != 0 && (st = drain()) != VKV_OK) return st;
+    p->sched_mode = mode;
     p->inflight_cap = max_inflight;
   }
+
   // one more launch may be enqueued once fewer than max_inflight are unfinished
   auto admit = [&]() -> int {
+    if (mode == 2) {
+      // launch n may go once launch n - max_inflight + 1 has started: then at most max_inflight - 1
+      // earlier launches are unfinished (one of them running)
+      const uint32_t n = p->launch_seq + 1;
+      if (n > (uint32_t)(max_inflight - 1)) wait_progress(p->progress_host, n - (uint32_t)(max_inflight - 1));
+      return VKV_OK;
+    }
     if (p->inflight_count == max_inflight) {
       VKV_HIP(hipEventSynchronize(p->inflight_ev[p->inflight_head]));
       p->inflight_head = (p->inflight_head + 1) % max_inflight;
@@ -148,11 +219,11 @@ int run_slices(vkv_pool* p, int32_t* cursor, int32_t n_slices, int32_t max_infli
     return VKV_OK;
   };
   auto track = [&](hipStream_t on) -> int {
+    if (mode == 2) return VKV_OK;
     VKV_HIP(hipEventRecord(p->inflight_ev[(p->inflight_head + p->inflight_count) % max_inflight], on));
     ++p->inflight_count;
     return VKV_OK;
   };
-  const bool two = p->overlap && p->aux_stream && max_inflight >= 2 && n_slices - *cursor >= 2;
   bool aux_used = false;
   if (two) {
     // the second stream starts after everything the caller has enqueued so far (q, tables, the plan upload)
@@ -168,43 +239,31 @@ int run_slices(vkv_pool* p, int32_t* cursor, int32_t n_slices, int32_t max_infli
     }
     return VKV_OK;
   };
+  auto yielded = [&](int32_t at) -> int {
+    int r = drain();
+    if (r != VKV_OK) return r;
+    if ((r = join()) != VKV_OK) return r;
+    *cursor = at;
+    return VKV_YIELDED;
+  };
   for (int32_t s = *cursor; s < n_slices; ++s) {
-    if (p->yield_flag.load(std::memory_order_acquire)) {
-      st = drain();
-      if (st != VKV_OK) return st;
-      if ((st = join()) != VKV_OK) return st;
-      *cursor = s;
-      return VKV_YIELDED;
-    }
+    if (p->yield_flag.load(std::memory_order_acquire)) return yielded(s);
     const hipStream_t on = (two && (s & 1)) ? p->aux_stream : hs;
     if ((st = admit()) != VKV_OK) return st;
     // admit() may have waited for up to one slice: a request that came in meanwhile is honoured now
-    if (p->yield_flag.load(std::memory_order_acquire)) {
-      st = drain();
-      if (st != VKV_OK) return st;
-      if ((st = join()) != VKV_OK) return st;
-      *cursor = s;
-      return VKV_YIELDED;
-    }
-    if ((st = launch(s, on)) != VKV_OK) return st;
+    if (p->yield_flag.load(std::memory_order_acquire)) return yielded(s);
+    p->report_seq = mode == 2 ? ++p->launch_seq : 0;
+    st = launch(s, on);
+    p->report_seq = 0;
+    if (st != VKV_OK) return st;
     if ((st = track(on)) != VKV_OK) return st;
     if (on != hs) aux_used = true;
   }
   if ((st = join()) != VKV_OK) return st;
   for (int32_t t = std::max(*cursor, n_slices) - n_slices; t < n_tail; ++t) {
-    if (p->yield_flag.load(std::memory_order_acquire)) {
-      st = drain();
-      if (st != VKV_OK) return st;
-      *cursor = n_slices + t;
-      return VKV_YIELDED;
-    }
+    if (p->yield_flag.load(std::memory_order_acquire)) return yielded(n_slices + t);
     if ((st = admit()) != VKV_OK) return st;
-    if (p->yield_flag.load(std::memory_order_acquire)) {
-      st = drain();
-      if (st != VKV_OK) return st;
-      *cursor = n_slices + t;
-      return VKV_YIELDED;
-    }
+    if (p->yield_flag.load(std::memory_order_acquire)) return yielded(n_slices + t);
     if ((st = tail(t)) != VKV_OK) return st;
     if ((st = track(hs)) != VKV_OK) return st;
   }
@@ -392,7 +451,7 @@ int kv_attn_run_layer(vkv_pool* p, int32_t layer, int32_t* cursor, const void* q
                     [&](int32_t s, hipStream_t on) {
                       return launch_slice(p, layer, s, q, table, max_blk, workspace, out, scale, on);
                     },
-                    0, nullptr);
+                    0, nullptr, true);
 }
 
 int paged_decode_attn_layer_static(vkv_pool* p, int32_t layer, const void* q, const int32_t* table, int32_t max_blk,

@@ -123,6 +123,7 @@ int kv_pool_destroy(vkv_pool* p) {
   // Best effort: report nothing, the process may be shutting the runtime down.
   if (p->stage) (void)hipHostFree(p->stage);
   if (p->remap_stage) (void)hipHostFree(p->remap_stage);
+  if (p->progress_host) (void)hipHostFree((void*)p->progress_host);
   if (p->stage_ev) (void)hipEventDestroy(p->stage_ev);
   if (p->remap_ev) (void)hipEventDestroy(p->remap_ev);
   if (p->grace_ev) (void)hipEventDestroy(p->grace_ev);
@@ -249,6 +250,14 @@ int kv_profile_enable(vkv_pool* p, int32_t max_records) {
     p->prof_ev.push_back(e);
   }
   p->prof_cap = max_records;
+  return VKV_OK;
+}
+
+int kv_profile_sample(vkv_pool* p, int32_t stride) {
+  if (!p || stride < 1) { set_error("kv_profile_sample: need a pool and stride >= 1"); return VKV_E_INVAL; }
+  std::lock_guard<std::mutex> g(p->prof_mu);
+  p->prof_stride = stride;
+  p->prof_tick = 0;
   return VKV_OK;
 }
 

@@ -628,7 +628,7 @@ int kv_prefill_run_layer(vkv_pool* p, int32_t layer, int32_t* cursor, const void
                       return pf_launch_slice(p, layer, s, q, table, max_blk, workspace, out, scale, on);
                     },
                     (int32_t)p->pf.merge_start.size() - 1,
-                    [&](int32_t step) { return pf_launch_merge(p, step, workspace, out, hs); });
+                    [&](int32_t step) { return pf_launch_merge(p, step, workspace, out, hs); }, false);
 }
 
 int kv_prefill_check(vkv_pool* p, void* workspace, void* stream) {

@@ -131,11 +131,22 @@ struct vkv_pool {
   hipEvent_t fork_ev = nullptr, join_ev = nullptr;
   int inflight_head = 0, inflight_count = 0, inflight_cap = 0;
   std::atomic<int> yield_flag{0};
+  // Progress words in pinned host memory that launches report to, so that the scheduler can bound
+  // its lead over the GPU without an event between every two launches (an event record keeps the
+  // next kernel from starting for several microseconds): word 0 = number of the newest launch that
+  // has started, word 1 = number of the newest drain marker that has run.
+  volatile uint32_t* progress_host = nullptr;
+  uint32_t* progress_dev = nullptr;
+  uint32_t launch_seq = 0;       // launches numbered so far (scheduler, one-stream mode)
+  uint32_t drain_seq = 0;        // drain markers numbered so far
+  uint32_t report_seq = 0;       // number the next launch_slice call reports, 0 = none
+  int sched_mode = 0;            // what bounds the lead now: 0 nothing yet, 1 event ring, 2 progress words
 
   // per-launch timing (kv_profile_enable)
   std::vector<hipEvent_t> prof_ev;      // 2 per record: start, end
   std::vector<std::pair<int32_t, int32_t>> prof_tag;   // (kind, index)
   int32_t prof_cap = 0;
+  int32_t prof_stride = 1, prof_tick = 0;   // only every prof_stride-th launch is bracketed
   std::mutex prof_mu;                  // the decode thread and the reclaim thread may both record
 
   bool broken = false;   // a HIP call failed mid-operation
@@ -155,7 +166,9 @@ struct ProfScope {
   ProfScope(vkv_pool* pool, int32_t kind, int32_t index, hipStream_t stream) : p(pool), st(stream) {
     if (p->prof_cap > 0) {
       std::lock_guard<std::mutex> g(p->prof_mu);
-      if ((int32_t)p->prof_tag.size() < p->prof_cap) {
+      // sampling thins out the many slice launches; the few other launches are always bracketed
+      const bool many = kind == VKV_PROF_SLICE || kind == VKV_PROF_PREFILL;
+      if ((!many || p->prof_tick++ % p->prof_stride == 0) && (int32_t)p->prof_tag.size() < p->prof_cap) {
         slot = (int)p->prof_tag.size();
         p->prof_tag.emplace_back(kind, index);
       }
@@ -176,7 +189,8 @@ int static_scratch_for_current_device(void** out);
 bool arena_range_mapped(const vkv_arena* a, int32_t first, int32_t last);
 int run_slices(vkv_pool* p, int32_t* cursor, int32_t n_slices, int32_t max_inflight, hipStream_t hs, const char* who,
                const std::function<int(int32_t, hipStream_t)>& launch, int32_t n_tail,
-               const std::function<int(int32_t)>& tail);
+               const std::function<int(int32_t)>& tail, bool launches_report);
+int ensure_progress_words(vkv_pool* p);
 
 // Host-side relocation plan; see kv_reclaim_plan.
 int plan_relocation(const vkv_pool* p, int32_t lo, int32_t hi,

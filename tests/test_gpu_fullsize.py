@@ -105,6 +105,9 @@ def test_stress_size_overlapped_slices_and_reclaim():
     the slices of a layer alternating between two streams: same bits as on one stream, sampled
     outputs against the oracle, reclamation of the top 16 GiB against the integer oracle."""
     from gpu_util import DeviceCase, oracle_attention_sampled
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()
     free, _ = torch.cuda.mem_get_info()
     wl = synth.workload("stress")
     if free < wl.geom.pool_bytes + (16 << 30):
@@ -155,5 +158,64 @@ def test_stress_size_overlapped_slices_and_reclaim():
         run_layers(c, layers, out)
         torch.cuda.synchronize()
         assert np.array_equal(out[layers].cpu().numpy(), one_stream)
+    finally:
+        c.close()
+
+
+@pytest.mark.parametrize("name", ["offline_batch", "llama70b_tp8"])
+def test_full_size_sampled_parity_of_the_other_configurations(name):
+    """The 160 GiB / context 32,768 shape and the 80-layer one-kv-head share, in the benchmark's launch
+    configuration (its chunk and slice sizes, slices overlapped where a layer has several): sampled
+    sequences against the oracle on the first and the last layer, every layer run bit-identical on a
+    second pass, and the reclamation of the top range against the integer oracle."""
+    from gpu_util import DeviceCase, oracle_attention_sampled
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()          # the pools of the tests before this one go back to the driver first
+    free, _ = torch.cuda.mem_get_info()
+    wl = synth.workload(name)
+    if free < wl.geom.pool_bytes + (16 << 30):
+        pytest.skip("not enough free HBM for this pool")
+    print(f"filling the {wl.geom.pool_bytes / 2**30:.0f} GiB pool", flush=True)
+    c = DeviceCase(wl, seed=2, host_pool=False)
+    try:
+        g, vkv = wl.geom, c.vkv
+        info = c.plan()
+        vkv.kv_sched_set_overlap(c.pool, info.n_slices > 1)
+        print(f"items {info.n_items} slices {info.n_slices} kv bytes/layer {info.kv_bytes_per_layer}", flush=True)
+        L = g.num_layers
+        layers = [0, L // 2, L - 1]
+        out = torch.full((L, wl.num_seqs, g.num_q_heads, g.head_dim), float("nan"), dtype=torch.float32, device="cuda:0")
+        run_layers(c, layers, out)
+        torch.cuda.synchronize()
+        first = out[layers].cpu().numpy()
+        assert np.isfinite(first).all()
+        out.fill_(float("nan"))
+        run_layers(c, layers, out)
+        torch.cuda.synchronize()
+        assert np.array_equal(out[layers].cpu().numpy(), first)
+        order = np.argsort(c.st.ctx_len)
+        seqs = [int(order[0]), int(order[len(order) // 2]), int(order[-1])]
+        for k, layer in ((0, layers[0]), (2, layers[2])):
+            ref = oracle_attention_sampled(wl, c.seed, c.st.tables, c.st.ctx_len, layer, seqs)
+            for s_ in seqs:
+                err = float(np.max(np.abs(first[k, s_].astype(np.float64) - ref[s_])))
+                print(f"{name} layer {layer} seq {s_} ctx {int(c.st.ctx_len[s_])}: max|err| {err:.3e}", flush=True)
+                assert err <= TOL
+        lo, hi = wl.reclaim_range
+        orc = R.ReclaimOracle(g.num_blocks, g.blocks_per_handle, c.st.live, c.st.tables, None)
+        stats = vkv.kv_reclaim_range(c.pool, lo, hi, c.tables_t, c.remap_t, chunk_bytes=wl.chunk_bytes)
+        status, src, dst, remap = orc.reclaim(lo, hi)
+        assert status == R.OK and stats.blocks_moved == len(src) > 1000
+        live, ranges = vkv.kv_pool_state(c.pool, g.num_blocks)
+        assert np.array_equal(live, orc.live) and ranges == [(lo, hi)]
+        assert np.array_equal(c.remap_t.cpu().numpy(), remap)
+        assert np.array_equal(c.tables_t.cpu().numpy(), orc.tables)
+        blocks = c.pool_t.view(g.num_blocks, g.block_elems)
+        blocks[lo:hi] = synth.BF16_NAN_BITS                     # the online tenant scribbles over its range
+        out.fill_(float("nan"))
+        run_layers(c, layers, out)
+        torch.cuda.synchronize()
+        assert np.array_equal(out[layers].cpu().numpy(), first)
     finally:
         c.close()

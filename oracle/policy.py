@@ -3,6 +3,7 @@
 selective_handles : Algorithm 1 ("selective memory reclamation", Section 5): k times pick the
                     handle whose not-yet-evicted requests cost least; ties go to the lowest
                     handle index (the paper leaves ties open).
+fifo_handles      : the FIFO baseline the paper compares Algorithm 1 with (Section 7.2).
 Miad              : the dynamic reservation of Section 5 ("Dynamic MIAD-style memory
                     reservation"): headroom H grows multiplicatively on a pressure event
                     (usage >= 90 % of H), shrinks by one handle every interval T otherwise;
@@ -49,6 +50,20 @@ def selective_handles(k: int, reqs, cost, candidates=None):
         total += best_cost
         evicted |= reqs[best]
     return chosen, evicted, total
+
+
+def fifo_handles(k: int, reqs, cost, candidates=None):
+    """The comparison policy of Section 7.2 ("evicts offline KV cache blocks in first-in-first-out
+    order"): in a pool that hands out its lowest free blocks first, the oldest blocks sit in the lowest
+    handles, so FIFO takes the first k candidate handles by index.  Same return as selective_handles."""
+    pool = list(range(len(reqs))) if candidates is None else list(candidates)
+    if k > len(pool):
+        raise ValueError("fewer candidate handles than k")
+    chosen = pool[:k]
+    evicted = set()
+    for h in chosen:
+        evicted |= reqs[h]
+    return chosen, evicted, sum(cost[r] for r in evicted)
 
 
 class Miad:

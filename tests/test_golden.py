@@ -243,3 +243,33 @@ def test_cooldown_traces_library():
             assert vkv.kv_gate_stats(g) == (tr["final"]["max_gap_s"], tr["final"]["preemptions"])
         finally:
             vkv.kv_gate_destroy(g)
+
+
+# ------------------------------------------------------------------ eviction by Algorithm 1, worked by hand
+def _eviction_oracle(ex, case):
+    return R.ReclaimOracle(ex["num_blocks"], ex["blocks_per_handle"], case["live"], case["tables"], None)
+
+
+def test_eviction_examples_oracle():
+    from oracle.policy import fifo_handles, handle_requests
+    ex = load("eviction_examples.json")
+    for case in ex["cases"]:
+        orc = _eviction_oracle(ex, case)
+        reqs = handle_requests(orc.tables, orc.nb, orc.bph)
+        fh, fe, ft = fifo_handles(case["k"], reqs, case["cost"])
+        assert (fh, sorted(fe), ft) == (case["fifo"]["handles"], case["fifo"]["evicted"], case["fifo"]["total"])
+        st, handles, evicted, inv, total = orc.evict(case["k"], case["cost"])
+        assert st == case["status"] and handles == case["handles"] and evicted == case["evicted"], case["name"]
+        assert total == case["total"] and [list(x) for x in inv] == case["invalidated"], case["name"]
+        assert orc.tables.tolist() == case["tables_after"] and orc.live.tolist() == case["live_after"], case["name"]
+        assert [list(r) for r in orc.released] == case["released_after"], case["name"]
+        assert total <= ft
+    roe = ex["reclaim_or_evict"]
+    orc = _eviction_oracle(ex, roe)
+    st, mode, payload = orc.reclaim_or_evict(*roe["range"], roe["cost"])
+    assert (st, mode) == (R.OK, roe["mode"]) and payload[0] == roe["handles"] and payload[1] == roe["evicted"]
+    assert orc.live.tolist() == roe["live_after"]
+    nxt = roe["then_relocation_fits"]
+    st, mode, payload = orc.reclaim_or_evict(*nxt["range"], roe["cost"])
+    assert (st, mode) == (R.OK, nxt["mode"])
+    assert [[int(a), int(b)] for a, b in zip(payload[0], payload[1])] == nxt["moves"]

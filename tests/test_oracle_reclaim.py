@@ -149,3 +149,89 @@ def test_unreferenced_live_blocks_are_moved_too():
     assert status == R.OK and src.tolist() == [30, 31] and dst.tolist() == [0, 1]
     assert orc.tables.tolist() == [[0, 3, -1]]
     assert orc.pool[1].tolist() == [124, 125, 126, 127]
+
+
+# ------------------------------------------------------------------ eviction (the paper's own hand-over)
+@pytest.mark.parametrize("seed", range(6))
+def test_eviction_invariants_on_random_pools(seed):
+    import synth
+    from oracle.policy import handle_requests
+    wl = synth.workload("tiny", occupancy=0.9, shared_prefix_blocks=2 if seed % 2 else 0)
+    st = synth.build_state(wl, seed, materialize_pool=False)
+    g = wl.geom
+    n_rows = st.tables.shape[0]
+    cost = [int((st.tables[r] >= 0).sum()) * 16 for r in range(n_rows)]
+    orc = R.ReclaimOracle(g.num_blocks, g.blocks_per_handle, st.live, st.tables, None)
+    before_tables, before_live = orc.tables.copy(), orc.live.copy()
+    reqs = handle_requests(before_tables, g.num_blocks, g.blocks_per_handle)
+    k = 3
+    status, handles, evicted, inv, total = orc.evict(k, cost)
+    assert status == R.OK and len(set(handles)) == k
+    bph = g.blocks_per_handle
+    chosen = set(handles)
+    # the evicted requests are exactly those with a block in a chosen handle, and their cost is the total
+    assert set(evicted) == set().union(*[reqs[h] for h in handles])
+    assert total == sum(cost[r] for r in evicted)
+    # invalidated entries = brute force over the old tables
+    want = [(r, c, int(before_tables[r, c])) for r in range(n_rows) for c in range(before_tables.shape[1])
+            if before_tables[r, c] >= 0 and int(before_tables[r, c]) // bph in chosen]
+    assert inv == want
+    # survivors keep their rows, evicted rows are empty, nobody names a chosen handle any more
+    for r in range(n_rows):
+        if r in evicted:
+            assert (orc.tables[r] == -1).all()
+        else:
+            assert np.array_equal(orc.tables[r], before_tables[r])
+    used = orc.tables[orc.tables >= 0]
+    assert not np.isin(used // bph, list(chosen)).any()
+    # every block a survivor names is still live; chosen handles are dead and handed over
+    assert orc.live[used].all()
+    for h in handles:
+        assert not orc.live[h * bph:(h + 1) * bph].any()
+    assert sorted(orc.released) == sorted((h * bph, (h + 1) * bph) for h in handles)
+    # nothing that was dead came alive, and blocks outside evicted rows and chosen handles are untouched
+    assert not (orc.live & ~before_live.astype(bool)).any()
+    gone = set(np.flatnonzero(before_live.astype(bool) & ~orc.live.astype(bool)).tolist())
+    ev_blocks = {int(e) for r in evicted for e in before_tables[r] if e >= 0}
+    handle_blocks = {b for h in handles for b in range(h * bph, (h + 1) * bph)}
+    assert gone <= ev_blocks | handle_blocks
+    # handed-over handles are no candidates any more; asking for more handles than are left fails whole
+    n_handles = g.num_blocks // bph
+    snap = (orc.tables.copy(), orc.live.copy(), list(orc.released))
+    assert orc.evict(n_handles - k + 1, cost)[0] == R.E_NOSPACE
+    assert np.array_equal(orc.tables, snap[0]) and np.array_equal(orc.live, snap[1]) and orc.released == snap[2]
+
+
+def test_selective_choice_costs_no_more_than_fifo():
+    """Section 7.2 compares Algorithm 1 with evicting in first-in-first-out order: for one handle the
+    greedy choice is the minimum, and over many fragmented pools it is cheaper in aggregate."""
+    import synth
+    from oracle.policy import fifo_handles, handle_requests, selective_handles
+    better = worse = 0
+    for seed in range(40):
+        wl = synth.workload("tiny", occupancy=0.7)
+        st = synth.build_state(wl, seed, materialize_pool=False)
+        g = wl.geom
+        reqs = handle_requests(st.tables, g.num_blocks, g.blocks_per_handle)
+        cost = {r: int((st.tables[r] >= 0).sum()) * 16 for r in range(st.tables.shape[0])}
+        for k in (1, 2, 4, 8):
+            _, _, sel = selective_handles(k, reqs, cost)
+            _, _, fifo = fifo_handles(k, reqs, cost)
+            if k == 1:
+                assert sel <= fifo
+            better += sel < fifo
+            worse += sel > fifo
+    assert better > 5 * max(1, worse)
+
+
+def test_return_of_part_of_a_range():
+    orc = R.ReclaimOracle(32, 4, [0] * 32, [[-1]], None)
+    assert orc.reclaim(8, 24)[0] == R.OK
+    assert orc.return_range(6, 10) == R.E_INVAL        # not inside one handed-over range
+    assert orc.return_range(9, 12) == R.E_INVAL        # not handle-aligned
+    assert orc.return_range(20, 24) == R.OK and orc.released == [(8, 20)]       # from the top
+    assert orc.return_range(12, 16) == R.OK and orc.released == [(8, 12), (16, 20)]   # from the middle: a split
+    assert orc.return_range(8, 12) == R.OK and orc.released == [(16, 20)]
+    assert orc.return_range(8, 12) == R.E_INVAL        # already back
+    assert orc.reclaim(16, 20)[0] == R.E_BUSY
+    assert orc.return_range(16, 20) == R.OK and orc.released == []

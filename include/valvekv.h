@@ -25,7 +25,8 @@
  *   - "device" pointers are HIP device memory owned by the caller; "host"
  *     pointers are ordinary host memory owned by the caller.  The library owns
  *     only the opaque vkv_pool object (host memory, small pinned staging
- *     buffers, HIP events).  It never allocates or frees device memory.
+ *     buffers, HIP events).  It never allocates or frees device memory; the one
+ *     exception, at the caller's request, is the kv_arena_* group.
  *   - Streams are hipStream_t passed as void* (NULL = the default stream).
  *     Device work is enqueued on the given stream; unless stated otherwise a
  *     call returns without waiting for it.
@@ -94,9 +95,11 @@ int kv_pool_alloc(vkv_pool* pool, int32_t n, int32_t* ids_out_host);
 int kv_pool_adopt(vkv_pool* pool, const int32_t* ids_host, int32_t n);
 int kv_pool_free(vkv_pool* pool, const int32_t* ids_host, int32_t n);
 
-/* The online tenant gives back a range obtained by kv_reclaim_range: its blocks
- * become free pool blocks again.  VKV_E_INVAL if [lo,hi) is not exactly a
- * handed-over range. */
+/* The online tenant gives back handles it holds: [lo,hi), a multiple of
+ * blocks_per_handle, must lie inside one handed-over range, which shrinks or
+ * splits accordingly (the dynamic reservation of Section 5 releases one handle at
+ * a time); the blocks become free pool blocks again.  VKV_E_INVAL otherwise;
+ * VKV_E_STATE if an arena is attached and the handles are unmapped. */
 int kv_pool_return_range(vkv_pool* pool, int32_t lo_block, int32_t hi_block);
 
 /* State read-back: live_out_host[NB] gets 1 for live blocks; ranges_out_host
@@ -270,6 +273,8 @@ int kv_reclaim_plan(vkv_pool* pool, int32_t lo_block, int32_t hi_block,
 
 #define VKV_RECLAIM_ASYNC 1u  /* return after enqueueing; the caller waits for copy_stream
                                  and guarantees that no slice is in flight */
+#define VKV_RECLAIM_NO_GRACE 2u /* the caller guarantees that no slice of this pool is in flight
+                                 on any stream: step 4 waits for copy_stream only */
 
 /* Hands block range [lo,hi) to the online tenant (Section 5: stop offline
  * compute first, pick handles, make them harmless, hand them over):
@@ -280,13 +285,17 @@ int kv_reclaim_plan(vkv_pool* pool, int32_t lo_block, int32_t hi_block,
  *      (the host thread sleeps; burst allowance = one chunk);
  *   3. rewrite block_tables (device int32, n_entries entries, -1 = empty) in
  *      place: entry e becomes remap[e];
- *   4. wait for copy_stream; if decode_stream is given, wait until the slices
- *      that were enqueued on it so far have finished (they may have read old
- *      entries, which still point at intact source blocks);
+ *   4. wait for copy_stream; then, unless decode_stream is the same stream as
+ *      copy_stream (stream order has done it already), wait until the work enqueued
+ *      on decode_stream so far has finished: slices launched before the rewrite may
+ *      have read old entries, which still point at intact source blocks.  NULL
+ *      names the default stream here as everywhere.  The second stream of
+ *      kv_sched_set_overlap, if there is one, is waited for in the same way;
  *   5. mark the range handed over.  From here no table entry and no later
  *      slice refers to it.
  * remap_dev: device int32 [NB] scratch, filled with the remap of this call.
- * With VKV_RECLAIM_ASYNC step 4 is skipped.
+ * With VKV_RECLAIM_ASYNC step 4 is skipped; with VKV_RECLAIM_NO_GRACE only its
+ * first part is done.
  * Concurrent slices on decode_stream stay correct throughout: copies only write
  * free blocks, and both old and new table entries name identical bytes.
  * Errors: as kv_reclaim_plan, VKV_E_HIP. */
@@ -384,19 +393,80 @@ int kv_select_handles(vkv_pool* pool, const int32_t* tables_host, int32_t n_rows
                       const int64_t* cost_host, int32_t k, int32_t* handles_out,
                       int32_t* evicted_rows_out, int32_t* n_evicted_out, int64_t* total_cost_out);
 
+/* What evicting a given set of handles would cost: evicted_rows_out (room for
+ * n_rows, ascending; may be NULL) = rows with an entry in one of the handles,
+ * *total_cost_out = sum of their cost.  For comparing policies, e.g. the
+ * first-in-first-out baseline of Section 7.2 (the first k handles not yet handed
+ * over).  Changes nothing.  Errors: VKV_E_INVAL. */
+int kv_handles_cost(vkv_pool* pool, const int32_t* tables_host, int32_t n_rows, int32_t max_blk,
+                    const int64_t* cost_host, const int32_t* handles_host, int32_t k,
+                    int32_t* evicted_rows_out, int32_t* n_evicted_out, int64_t* total_cost_out);
+
 /* Hands the given handles to the online tenant WITHOUT saving their contents
- * (the paper's way, Section 5: the fallback of this library when relocation
- * finds no room): their blocks stop being live, each handle becomes a
- * handed-over range [h*bph, (h+1)*bph), and every table entry that named one of
+ * (the paper's way, Section 5): their blocks stop being live, each handle becomes
+ * a handed-over range [h*bph, (h+1)*bph), and every table entry that named one of
  * their blocks is reported as (row, column, block id) in row-major order: the
  * invalidated ids the framework needs to requeue the affected requests
  * (their remaining blocks are the framework's to free).  If more than `cap`
  * entries are affected, *n_inv_out gets the number needed, VKV_E_NOSPACE is
- * returned and nothing changes.  Errors: VKV_E_INVAL, VKV_E_BUSY, VKV_E_NOSPACE. */
+ * returned and nothing changes.
+ * tables_dev (device copy of the same tables, may be NULL): when given, the
+ * affected entries become -1 there too (an entry the kernels skip and flag), on
+ * `stream`, using remap_dev (device int32 [NB]) as scratch, and the call waits for
+ * `stream` and, as kv_reclaim_range does, for the slices already enqueued on
+ * decode_stream: from then on nothing reads the handles, and they may be
+ * unmapped (kv_arena_release).  Without tables_dev the library cannot know what
+ * the device tables say, and kv_arena_release refuses these ranges.
+ * Errors: VKV_E_INVAL, VKV_E_BUSY, VKV_E_NOSPACE, VKV_E_HIP. */
 int kv_invalidate_handles(vkv_pool* pool, const int32_t* handles_host, int32_t k,
                           const int32_t* tables_host, int32_t n_rows, int32_t max_blk,
                           int32_t* inv_row_out, int32_t* inv_col_out, int32_t* inv_block_out,
-                          int32_t cap, int32_t* n_inv_out);
+                          int32_t cap, int32_t* n_inv_out,
+                          int32_t* tables_dev, int32_t* remap_dev, void* stream, void* decode_stream);
+
+typedef struct vkv_evict_info {
+  int32_t mode;                 /* 0: the range was emptied by relocation; 1: handles were evicted */
+  int32_t n_handles;            /* handles handed over by eviction */
+  int32_t n_evicted;            /* requests (table rows) evicted */
+  int32_t n_invalidated;        /* table entries that named a block of an evicted handle */
+  int64_t total_cost;           /* sum of Cost(r) over the evicted requests */
+} vkv_evict_info;
+
+/* Eviction as one call (Section 5, "Sub-layer memory reclamation" and "Selective
+ * handle reclamation"): k handles are chosen by Algorithm 1 as in
+ * kv_select_handles and handed over without saving their contents; every request
+ * (row) with a block in one of them is evicted whole: its row is cleared in
+ * tables_host (updated in place) and, when given, in tables_dev (on `stream`, with
+ * scratch_dev, device int32 [>= n_rows], as scratch; then `stream` and the slices
+ * already enqueued on decode_stream are waited for); its blocks outside the chosen
+ * handles are freed unless a surviving row still names them; every block of a
+ * chosen handle dies.  handles_out[k] in pick order; evicted_rows_out (room for
+ * n_rows, ascending, may be NULL); the invalidated entries as for
+ * kv_invalidate_handles (lists may be NULL; more than `cap` of them: VKV_E_NOSPACE,
+ * info->n_invalidated says how many, nothing changes).  The evicted requests are
+ * the framework's to requeue; plan the next decode step with their context length
+ * set to 0.  Errors: VKV_E_INVAL, VKV_E_NOSPACE (also: fewer than k handles left),
+ * VKV_E_HIP. */
+int kv_evict_handles(vkv_pool* pool, int32_t k, int32_t* tables_host, int32_t n_rows, int32_t max_blk,
+                     const int64_t* cost_host, int32_t* tables_dev, int32_t* scratch_dev,
+                     void* stream, void* decode_stream,
+                     int32_t* handles_out, int32_t* evicted_rows_out,
+                     int32_t* inv_row_out, int32_t* inv_col_out, int32_t* inv_block_out, int32_t cap,
+                     vkv_evict_info* info_out);
+
+/* Hands (hi - lo) / blocks_per_handle handles to the online tenant: by emptying
+ * [lo,hi) as kv_reclaim_range does when the free blocks elsewhere suffice (then
+ * tables_host follows the rewrite of tables_dev), otherwise, instead of failing
+ * with VKV_E_NOSPACE, by kv_evict_handles of that many handles (not necessarily
+ * those of [lo,hi): the ones that cost least).  info_out->mode says which.
+ * Arguments as for the two calls; remap_dev doubles as the eviction's scratch. */
+int kv_reclaim_or_evict(vkv_pool* pool, int32_t lo_block, int32_t hi_block,
+                        int32_t* tables_dev, int32_t* tables_host, int32_t n_rows, int32_t max_blk,
+                        const int64_t* cost_host, uint64_t chunk_bytes, uint64_t rate_cap_bytes_per_s,
+                        void* copy_stream, void* decode_stream, int32_t* remap_dev, uint32_t flags,
+                        int32_t* handles_out, int32_t* evicted_rows_out,
+                        int32_t* inv_row_out, int32_t* inv_col_out, int32_t* inv_block_out, int32_t cap,
+                        vkv_evict_info* info_out, vkv_reclaim_stats* stats_out);
 
 /* Dynamic reservation (Section 5, "Dynamic MIAD-style memory reservation"): the
  * online tenant's headroom H, in handles.  The paper fixes only the 90 %
@@ -501,12 +571,14 @@ int kv_arena_destroy(vkv_arena* arena);
 int kv_pool_attach_arena(vkv_pool* pool, vkv_arena* arena);
 
 /* Unmaps the handles of [lo_block, hi_block) and releases their physical
- * memory.  The range must be one that kv_reclaim_range (or
- * kv_invalidate_handles) has handed over and that has not been returned: by
- * then the copy, the table rewrite and the grace wait are over, and the
- * allocator, the planner and every block table avoid it.  Any later access to
- * it is a GPU fault.  Errors: VKV_E_INVAL (arena not attached to this pool),
- * VKV_E_STATE (not a handed-over range, or already unmapped), VKV_E_HIP. */
+ * memory.  The range (a multiple of blocks_per_handle) must lie inside one that
+ * kv_reclaim_range, kv_evict_handles or kv_invalidate_handles has handed over
+ * WITH the device block tables in hand and that has not been returned: by then
+ * the copy or the clearing, the table rewrite and the grace wait are over, and
+ * the allocator, the planner and every block table the library was shown avoid
+ * it.  Any later access to it is a GPU fault.  Errors: VKV_E_INVAL (arena not
+ * attached to this pool, bad range), VKV_E_STATE (not handed over, handed over
+ * without the device tables, or already unmapped), VKV_E_HIP. */
 int kv_arena_release(vkv_arena* arena, vkv_pool* pool, int32_t lo_block, int32_t hi_block);
 
 /* Maps fresh physical memory (contents undefined) behind the handles of a

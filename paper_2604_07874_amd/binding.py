@@ -14,7 +14,8 @@ import numpy as np
 
 __all__ = [
     "VKV_OK", "VKV_YIELDED", "VKV_E_INVAL", "VKV_E_NOSPACE", "VKV_E_BUSY", "VKV_E_HIP", "VKV_E_STATE",
-    "VKV_RECLAIM_ASYNC", "VkvError", "PoolConfig", "AttnPlanInfo", "ReclaimStats", "lib", "library_path",
+    "VKV_RECLAIM_ASYNC", "VKV_RECLAIM_NO_GRACE", "VkvError", "EvictInfo", "kv_handles_cost", "kv_evict_handles",
+    "kv_reclaim_or_evict", "PoolConfig", "AttnPlanInfo", "ReclaimStats", "lib", "library_path",
     "last_error", "kv_pool_init", "kv_pool_destroy", "kv_pool_alloc", "kv_pool_adopt", "kv_pool_free",
     "kv_pool_return_range", "kv_pool_state", "kv_pool_check_tables", "kv_attn_plan", "kv_attn_plan_read",
     "kv_attn_bind", "paged_decode_attn_slice", "kv_attn_check", "kv_attn_run_layer",
@@ -34,6 +35,7 @@ __all__ = [
 VKV_OK, VKV_YIELDED = 0, 1
 VKV_E_INVAL, VKV_E_NOSPACE, VKV_E_BUSY, VKV_E_HIP, VKV_E_STATE = -1, -2, -3, -4, -5
 VKV_RECLAIM_ASYNC = 1
+VKV_RECLAIM_NO_GRACE = 2
 VKV_PROF_SLICE, VKV_PROF_RELOCATE, VKV_PROF_REWRITE, VKV_PROF_PREFILL, VKV_PROF_PREFILL_MERGE = 0, 1, 2, 3, 4
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -75,6 +77,11 @@ class PrefillPlanInfo(C.Structure):
                 ("tile_positions", C.c_int32), ("total_q", C.c_int32), ("n_merge_steps", C.c_int32),
                 ("workspace_bytes", C.c_uint64), ("kv_bytes_per_layer", C.c_uint64),
                 ("max_slice_kv_bytes", C.c_uint64), ("flops_per_layer", C.c_double)]
+
+
+class EvictInfo(C.Structure):
+    _fields_ = [("mode", C.c_int32), ("n_handles", C.c_int32), ("n_evicted", C.c_int32), ("n_invalidated", C.c_int32),
+                ("total_cost", C.c_int64)]
 
 
 class MiadConfig(C.Structure):
@@ -134,7 +141,14 @@ _sigs = {
     "kv_prefill_run_layer": (C.c_int, [_P, C.c_int32, _I32P, _P, _P, C.c_int32, _P, _P, C.c_float, C.c_int32, _P]),
     "kv_prefill_check": (C.c_int, [_P, _P, _P]),
     "kv_select_handles": (C.c_int, [_P, _P, C.c_int32, C.c_int32, _P, C.c_int32, _P, _P, _I32P, C.POINTER(C.c_int64)]),
-    "kv_invalidate_handles": (C.c_int, [_P, _P, C.c_int32, _P, C.c_int32, C.c_int32, _P, _P, _P, C.c_int32, _I32P]),
+    "kv_invalidate_handles": (C.c_int, [_P, _P, C.c_int32, _P, C.c_int32, C.c_int32, _P, _P, _P, C.c_int32, _I32P,
+                                        _P, _P, _P, _P]),
+    "kv_handles_cost": (C.c_int, [_P, _P, C.c_int32, C.c_int32, _P, _P, C.c_int32, _P, _I32P, C.POINTER(C.c_int64)]),
+    "kv_evict_handles": (C.c_int, [_P, C.c_int32, _P, C.c_int32, C.c_int32, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P,
+                                   C.c_int32, C.POINTER(EvictInfo)]),
+    "kv_reclaim_or_evict": (C.c_int, [_P, C.c_int32, C.c_int32, _P, _P, C.c_int32, C.c_int32, _P, C.c_uint64, C.c_uint64,
+                                      _P, _P, _P, C.c_uint32, _P, _P, _P, _P, _P, C.c_int32, C.POINTER(EvictInfo),
+                                      C.POINTER(ReclaimStats)]),
     "kv_miad_init": (C.c_int, [C.POINTER(MiadConfig), C.POINTER(_P)]),
     "kv_miad_destroy": (C.c_int, [_P]),
     "kv_miad_observe": (C.c_int, [_P, C.c_double, C.c_int32, C.POINTER(MiadStep)]),
@@ -473,7 +487,8 @@ def kv_select_handles(pool, tables_host, cost_host, k: int):
     return handles, ev[:n_ev.value].copy(), total.value
 
 
-def kv_invalidate_handles(pool, handles, tables_host, cap=None):
+def kv_invalidate_handles(pool, handles, tables_host, cap=None, tables_dev=None, remap_dev=None, stream=None,
+                          decode_stream=None):
     """Returns (rows, columns, block ids) of the invalidated table entries, row-major order."""
     t = _host(tables_host, np.int32)
     n_rows, max_blk = t.shape
@@ -482,8 +497,68 @@ def kv_invalidate_handles(pool, handles, tables_host, cap=None):
     rows, cols, blks = (np.empty(cap, dtype=np.int32) for _ in range(3))
     n = C.c_int32(0)
     _check(lib.kv_invalidate_handles(pool, h.ctypes.data, len(h), t.ctypes.data, n_rows, max_blk, rows.ctypes.data,
-                                     cols.ctypes.data, blks.ctypes.data, cap, C.byref(n)))
+                                     cols.ctypes.data, blks.ctypes.data, cap, C.byref(n), _dev(tables_dev),
+                                     _dev(remap_dev), _stream(stream) if tables_dev is not None else None,
+                                     _stream(decode_stream) if decode_stream is not None else None))
     return rows[:n.value].copy(), cols[:n.value].copy(), blks[:n.value].copy()
+
+
+def kv_handles_cost(pool, tables_host, cost_host, handles):
+    """Returns (rows with an entry in one of the handles, sum of their cost)."""
+    t = _host(tables_host, np.int32)
+    n_rows, max_blk = t.shape
+    cost = _host(cost_host, np.int64)
+    h = _host(handles, np.int32)
+    ev = np.empty(n_rows, dtype=np.int32)
+    n_ev, total = C.c_int32(0), C.c_int64(0)
+    _check(lib.kv_handles_cost(pool, t.ctypes.data, n_rows, max_blk, cost.ctypes.data, h.ctypes.data, len(h),
+                               ev.ctypes.data, C.byref(n_ev), C.byref(total)))
+    return ev[:n_ev.value].copy(), total.value
+
+
+def kv_evict_handles(pool, k: int, tables_host, cost_host, tables_dev=None, scratch_dev=None, stream=None,
+                     decode_stream=None, cap=None):
+    """tables_host (int32 [n_rows, max_blk], C-contiguous) is updated in place.
+    Returns (info, handles, evicted rows, (rows, columns, block ids) of the invalidated entries)."""
+    t = tables_host
+    assert t.dtype == np.int32 and t.flags.c_contiguous and t.ndim == 2
+    n_rows, max_blk = t.shape
+    cost = _host(cost_host, np.int64)
+    cap = t.size if cap is None else cap
+    handles = np.empty(max(k, 1), dtype=np.int32)
+    ev = np.empty(max(n_rows, 1), dtype=np.int32)
+    rows, cols, blks = (np.empty(max(cap, 1), dtype=np.int32) for _ in range(3))
+    info = EvictInfo()
+    _check(lib.kv_evict_handles(pool, k, t.ctypes.data, n_rows, max_blk, cost.ctypes.data, _dev(tables_dev),
+                                _dev(scratch_dev), _stream(stream) if tables_dev is not None else None,
+                                _stream(decode_stream) if decode_stream is not None else None,
+                                handles.ctypes.data, ev.ctypes.data, rows.ctypes.data, cols.ctypes.data, blks.ctypes.data,
+                                cap, C.byref(info)))
+    n = info.n_invalidated
+    return info, handles[:k].copy(), ev[:info.n_evicted].copy(), (rows[:n].copy(), cols[:n].copy(), blks[:n].copy())
+
+
+def kv_reclaim_or_evict(pool, lo: int, hi: int, tables_dev, tables_host, cost_host, remap_dev, chunk_bytes: int = 0,
+                        rate_cap_bytes_per_s: int = 0, copy_stream=None, decode_stream=None, flags: int = 0, cap=None):
+    """Returns (info, stats, handles, evicted rows, invalidated entries); tables_host is updated in place."""
+    t = tables_host
+    assert t.dtype == np.int32 and t.flags.c_contiguous and t.ndim == 2
+    n_rows, max_blk = t.shape
+    cost = _host(cost_host, np.int64)
+    cap = t.size if cap is None else cap
+    k = max(1, hi - lo)
+    handles = np.empty(k, dtype=np.int32)
+    ev = np.empty(max(n_rows, 1), dtype=np.int32)
+    rows, cols, blks = (np.empty(max(cap, 1), dtype=np.int32) for _ in range(3))
+    info, stats = EvictInfo(), ReclaimStats()
+    ds = None if decode_stream is None else _stream(decode_stream)
+    _check(lib.kv_reclaim_or_evict(pool, lo, hi, _dev(tables_dev), t.ctypes.data, n_rows, max_blk, cost.ctypes.data,
+                                   chunk_bytes, int(rate_cap_bytes_per_s), _stream(copy_stream), ds, _dev(remap_dev), flags,
+                                   handles.ctypes.data, ev.ctypes.data, rows.ctypes.data, cols.ctypes.data,
+                                   blks.ctypes.data, cap, C.byref(info), C.byref(stats)))
+    n = info.n_invalidated
+    return (info, stats, handles[:info.n_handles].copy(), ev[:info.n_evicted].copy(),
+            (rows[:n].copy(), cols[:n].copy(), blks[:n].copy()))
 
 
 def kv_miad_init(**kw):

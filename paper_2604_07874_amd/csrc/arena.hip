@@ -60,7 +60,7 @@ bool arena_range_mapped(const vkv_arena* a, int32_t first, int32_t last) {
   return true;
 }
 
-// the arena backs exactly this pool, and [lo, hi) is one of its handed-over ranges
+// the arena backs exactly this pool, and [lo, hi) lies inside one of its handed-over ranges whose tables are clean
 static int check_pair(const vkv_arena* a, const vkv_pool* p, int32_t lo, int32_t hi, const char* who) {
   if (!a || !p) { set_error("%s: null arena or pool", who); return VKV_E_INVAL; }
   if (p->arena != a || (char*)p->cfg.base != a->base ||
@@ -69,9 +69,21 @@ static int check_pair(const vkv_arena* a, const vkv_pool* p, int32_t lo, int32_t
     set_error("%s: the arena is not attached to this pool (kv_pool_attach_arena)", who);
     return VKV_E_INVAL;
   }
+  const int32_t bph = p->cfg.blocks_per_handle;
+  if (lo < 0 || hi > p->cfg.num_blocks || lo >= hi || lo % bph || hi % bph) {
+    set_error("%s: [%d,%d) must be non-empty, inside the pool and a multiple of %d blocks", who, lo, hi, bph);
+    return VKV_E_INVAL;
+  }
   for (const auto& r : p->released)
-    if (r.first == lo && r.second == hi) return VKV_OK;
-  set_error("%s: [%d,%d) is not a handed-over range of the pool", who, lo, hi);
+    if (r.first <= lo && hi <= r.second) {
+      if (!r.clean) {
+        set_error("%s: [%d,%d) was handed over without the device block tables being rewritten; slices may still "
+                  "read it", who, lo, hi);
+        return VKV_E_STATE;
+      }
+      return VKV_OK;
+    }
+  set_error("%s: [%d,%d) does not lie inside a handed-over range of the pool", who, lo, hi);
   return VKV_E_STATE;
 }
 

@@ -43,27 +43,22 @@ static void handle_rows(const vkv_pool* p, const int32_t* tables, int32_t n_rows
     }
 }
 
-extern "C" {
+namespace vkv {
 
-int kv_select_handles(vkv_pool* p, const int32_t* tables, int32_t n_rows, int32_t max_blk, const int64_t* cost,
-                      int32_t k, int32_t* handles_out, int32_t* evicted_rows_out, int32_t* n_evicted_out,
-                      int64_t* total_cost_out) {
-  if (!p || n_rows < 0 || max_blk < 0 || (n_rows > 0 && max_blk > 0 && !tables) || (n_rows > 0 && !cost) || k < 0 ||
-      (k > 0 && !handles_out)) {
-    set_error("kv_select_handles: bad argument");
-    return VKV_E_INVAL;
-  }
+int select_handles_impl(const vkv_pool* p, const int32_t* tables, int32_t n_rows, int32_t max_blk, const int64_t* cost,
+                        int32_t k, int32_t* handles_out, std::vector<uint8_t>& evicted, int64_t* total_out, const char* who) {
   const int32_t bph = p->cfg.blocks_per_handle, n_handles = p->cfg.num_blocks / bph;
   std::vector<std::vector<int32_t>> reqs;
   handle_rows(p, tables, n_rows, max_blk, reqs);
-  std::vector<uint8_t> candidate((size_t)n_handles, 1), evicted((size_t)n_rows, 0);
+  std::vector<uint8_t> candidate((size_t)n_handles, 1);
+  evicted.assign((size_t)n_rows, 0);
   int32_t n_cand = 0;
   for (int32_t h = 0; h < n_handles; ++h) {
     if (in_released(p, h * bph)) candidate[(size_t)h] = 0;   // already with the online tenant
     n_cand += candidate[(size_t)h];
   }
   if (k > n_cand) {
-    set_error("kv_select_handles: %d handles wanted, %d not yet handed over", k, n_cand);
+    set_error("%s: %d handles wanted, %d not yet handed over", who, k, n_cand);
     return VKV_E_NOSPACE;
   }
   int64_t total = 0;
@@ -82,6 +77,53 @@ int kv_select_handles(vkv_pool* p, const int32_t* tables, int32_t n_rows, int32_
     total += best_cost;
     for (int32_t r : reqs[(size_t)best]) evicted[(size_t)r] = 1;
   }
+  if (total_out) *total_out = total;
+  return VKV_OK;
+}
+
+// one row of a device block table per workgroup: every entry becomes -1
+__global__ __launch_bounds__(256) void table_clear_rows_kernel(int32_t* __restrict__ tables, int32_t max_blk,
+                                                                const int32_t* __restrict__ rows) {
+  int32_t* row = tables + (size_t)rows[blockIdx.x] * max_blk;
+  for (int32_t j = threadIdx.x; j < max_blk; j += blockDim.x) row[j] = -1;
+}
+
+}  // namespace vkv
+
+static bool bad_tables(int32_t n_rows, int32_t max_blk, const int32_t* tables) {
+  return n_rows < 0 || max_blk < 0 || (n_rows > 0 && max_blk > 0 && !tables);
+}
+
+// Entries of the host tables that name a block of a chosen handle, row-major; count only when the outputs are NULL.
+static int64_t list_invalidated(const vkv_pool* p, const std::vector<uint8_t>& chosen, const int32_t* tables, int32_t n_rows,
+                                int32_t max_blk, int32_t* rows, int32_t* cols, int32_t* blks) {
+  const int32_t bph = p->cfg.blocks_per_handle;
+  int64_t n = 0;
+  for (int32_t r = 0; r < n_rows; ++r)
+    for (int32_t j = 0; j < max_blk; ++j) {
+      const int32_t e = tables[(size_t)r * max_blk + j];
+      if (e >= 0 && e < p->cfg.num_blocks && chosen[(size_t)(e / bph)]) {
+        if (rows) rows[n] = r;
+        if (cols) cols[n] = j;
+        if (blks) blks[n] = e;
+        ++n;
+      }
+    }
+  return n;
+}
+
+extern "C" {
+
+int kv_select_handles(vkv_pool* p, const int32_t* tables, int32_t n_rows, int32_t max_blk, const int64_t* cost,
+                      int32_t k, int32_t* handles_out, int32_t* evicted_rows_out, int32_t* n_evicted_out,
+                      int64_t* total_cost_out) {
+  if (!p || bad_tables(n_rows, max_blk, tables) || (n_rows > 0 && !cost) || k < 0 || (k > 0 && !handles_out)) {
+    set_error("kv_select_handles: bad argument");
+    return VKV_E_INVAL;
+  }
+  std::vector<uint8_t> evicted;
+  int st = select_handles_impl(p, tables, n_rows, max_blk, cost, k, handles_out, evicted, total_cost_out, "kv_select_handles");
+  if (st != VKV_OK) return st;
   int32_t n_ev = 0;
   for (int32_t r = 0; r < n_rows; ++r)
     if (evicted[(size_t)r]) {
@@ -89,19 +131,52 @@ int kv_select_handles(vkv_pool* p, const int32_t* tables, int32_t n_rows, int32_
       ++n_ev;
     }
   if (n_evicted_out) *n_evicted_out = n_ev;
+  return VKV_OK;
+}
+
+int kv_handles_cost(vkv_pool* p, const int32_t* tables, int32_t n_rows, int32_t max_blk, const int64_t* cost,
+                    const int32_t* handles, int32_t k, int32_t* evicted_rows_out, int32_t* n_evicted_out,
+                    int64_t* total_cost_out) {
+  if (!p || bad_tables(n_rows, max_blk, tables) || (n_rows > 0 && !cost) || k < 0 || (k > 0 && !handles)) {
+    set_error("kv_handles_cost: bad argument");
+    return VKV_E_INVAL;
+  }
+  const int32_t bph = p->cfg.blocks_per_handle, n_handles = p->cfg.num_blocks / bph;
+  std::vector<uint8_t> chosen((size_t)n_handles, 0);
+  for (int32_t i = 0; i < k; ++i) {
+    if (handles[i] < 0 || handles[i] >= n_handles) { set_error("kv_handles_cost: bad handle %d", handles[i]); return VKV_E_INVAL; }
+    chosen[(size_t)handles[i]] = 1;
+  }
+  int32_t n_ev = 0;
+  int64_t total = 0;
+  for (int32_t r = 0; r < n_rows; ++r) {
+    bool hit = false;
+    for (int32_t j = 0; j < max_blk && !hit; ++j) {
+      const int32_t e = tables[(size_t)r * max_blk + j];
+      hit = e >= 0 && e < p->cfg.num_blocks && chosen[(size_t)(e / bph)];
+    }
+    if (hit) {
+      if (evicted_rows_out) evicted_rows_out[n_ev] = r;
+      ++n_ev;
+      total += cost[r];
+    }
+  }
+  if (n_evicted_out) *n_evicted_out = n_ev;
   if (total_cost_out) *total_cost_out = total;
   return VKV_OK;
 }
 
 int kv_invalidate_handles(vkv_pool* p, const int32_t* handles, int32_t k, const int32_t* tables, int32_t n_rows,
                           int32_t max_blk, int32_t* inv_row_out, int32_t* inv_col_out, int32_t* inv_block_out,
-                          int32_t cap, int32_t* n_inv_out) {
-  if (!p || k < 0 || (k > 0 && !handles) || n_rows < 0 || max_blk < 0 || (n_rows > 0 && max_blk > 0 && !tables) ||
-      cap < 0 || !n_inv_out) {
+                          int32_t cap, int32_t* n_inv_out, int32_t* tables_dev, int32_t* remap_dev, void* stream_v,
+                          void* decode_stream_v) {
+  if (!p || k < 0 || (k > 0 && !handles) || bad_tables(n_rows, max_blk, tables) || cap < 0 || !n_inv_out ||
+      (tables_dev && !remap_dev)) {
     set_error("kv_invalidate_handles: bad argument");
     return VKV_E_INVAL;
   }
-  const int32_t bph = p->cfg.blocks_per_handle, n_handles = p->cfg.num_blocks / bph;
+  if (tables_dev && p->broken) { set_error("kv_invalidate_handles: pool unusable after a HIP failure"); return VKV_E_HIP; }
+  const int32_t bph = p->cfg.blocks_per_handle, n_handles = p->cfg.num_blocks / bph, nb = p->cfg.num_blocks;
   std::vector<uint8_t> chosen((size_t)n_handles, 0);
   for (int32_t i = 0; i < k; ++i) {
     const int32_t h = handles[i];
@@ -110,36 +185,138 @@ int kv_invalidate_handles(vkv_pool* p, const int32_t* handles, int32_t k, const 
     chosen[(size_t)h] = 1;
   }
   // count first, so that a too small output leaves everything untouched
-  int64_t n_inv = 0;
-  for (int32_t r = 0; r < n_rows; ++r)
-    for (int32_t j = 0; j < max_blk; ++j) {
-      const int32_t e = tables[(size_t)r * max_blk + j];
-      if (e >= 0 && e < p->cfg.num_blocks && chosen[(size_t)(e / bph)]) ++n_inv;
-    }
+  const int64_t n_inv = list_invalidated(p, chosen, tables, n_rows, max_blk, nullptr, nullptr, nullptr);
   if (n_inv > cap) {
     *n_inv_out = (int32_t)std::min<int64_t>(n_inv, 0x7FFFFFFF);
     set_error("kv_invalidate_handles: %lld invalidated entries, room for %d", (long long)n_inv, cap);
     return VKV_E_NOSPACE;
   }
-  int32_t w = 0;
-  for (int32_t r = 0; r < n_rows; ++r)
-    for (int32_t j = 0; j < max_blk; ++j) {
-      const int32_t e = tables[(size_t)r * max_blk + j];
-      if (e >= 0 && e < p->cfg.num_blocks && chosen[(size_t)(e / bph)]) {
-        if (inv_row_out) inv_row_out[w] = r;
-        if (inv_col_out) inv_col_out[w] = j;
-        if (inv_block_out) inv_block_out[w] = e;
-        ++w;
-      }
-    }
-  *n_inv_out = w;
+  if (tables_dev) {
+    // The device tables lose the entries too (they become -1, which the kernels skip and flag), and the
+    // slices that may still hold the old entries are waited for: from then on nothing reads the handles.
+    hipStream_t cs = (hipStream_t)stream_v;
+    int st = ensure_remap_stage(p);
+    if (st != VKV_OK) return st;
+    for (int32_t b = 0; b < nb; ++b) p->remap_stage[b] = chosen[(size_t)(b / bph)] ? -1 : b;
+    auto fail = [&](int code) { p->broken = true; return code; };
+    hipError_t he = hipMemcpyAsync(remap_dev, p->remap_stage, (size_t)nb * 4, hipMemcpyHostToDevice, cs);
+    if (he != hipSuccess) return fail(hip_fail(he, "remap upload"));
+    if (launch_rewrite(p, tables_dev, (int64_t)n_rows * max_blk, remap_dev, nb, cs) != VKV_OK) return fail(VKV_E_HIP);
+    he = hipStreamSynchronize(cs);
+    if (he != hipSuccess) return fail(hip_fail(he, "hipStreamSynchronize"));
+    if (grace_wait(p, cs, (hipStream_t)decode_stream_v) != VKV_OK) return fail(VKV_E_HIP);
+  }
+  *n_inv_out = (int32_t)list_invalidated(p, chosen, tables, n_rows, max_blk, inv_row_out, inv_col_out, inv_block_out);
   for (int32_t h = 0; h < n_handles; ++h) {
     if (!chosen[(size_t)h]) continue;
     for (int32_t b = h * bph; b < (h + 1) * bph; ++b)
       if (p->live[(size_t)b]) { p->live[(size_t)b] = 0; --p->n_live; }
-    p->released.emplace_back(h * bph, (h + 1) * bph);
   }
+  for (int32_t i = 0; i < k; ++i)   // in the order given
+    p->released.emplace_back(handles[i] * bph, (handles[i] + 1) * bph, tables_dev != nullptr);
   return VKV_OK;
+}
+
+int kv_evict_handles(vkv_pool* p, int32_t k, int32_t* tables, int32_t n_rows, int32_t max_blk, const int64_t* cost,
+                     int32_t* tables_dev, int32_t* scratch_dev, void* stream_v, void* decode_stream_v,
+                     int32_t* handles_out, int32_t* evicted_rows_out, int32_t* inv_row_out, int32_t* inv_col_out,
+                     int32_t* inv_block_out, int32_t cap, vkv_evict_info* info) {
+  if (!p || k < 0 || (k > 0 && !handles_out) || bad_tables(n_rows, max_blk, tables) || (n_rows > 0 && !cost) || cap < 0 ||
+      !info || (tables_dev && !scratch_dev)) {
+    set_error("kv_evict_handles: bad argument");
+    return VKV_E_INVAL;
+  }
+  if (tables_dev && p->broken) { set_error("kv_evict_handles: pool unusable after a HIP failure"); return VKV_E_HIP; }
+  const int32_t bph = p->cfg.blocks_per_handle, n_handles = p->cfg.num_blocks / bph, nb = p->cfg.num_blocks;
+  if (tables_dev && n_rows > nb) { set_error("kv_evict_handles: more table rows than blocks"); return VKV_E_INVAL; }
+  std::vector<uint8_t> evicted;
+  int64_t total = 0;
+  int st = select_handles_impl(p, tables, n_rows, max_blk, cost, k, handles_out, evicted, &total, "kv_evict_handles");
+  if (st != VKV_OK) return st;
+  std::vector<uint8_t> chosen((size_t)n_handles, 0);
+  for (int32_t i = 0; i < k; ++i) chosen[(size_t)handles_out[i]] = 1;
+  const int64_t n_inv = list_invalidated(p, chosen, tables, n_rows, max_blk, nullptr, nullptr, nullptr);
+  *info = vkv_evict_info{};
+  info->n_invalidated = (int32_t)std::min<int64_t>(n_inv, 0x7FFFFFFF);
+  if (n_inv > cap) {
+    set_error("kv_evict_handles: %lld invalidated entries, room for %d", (long long)n_inv, cap);
+    return VKV_E_NOSPACE;
+  }
+  std::vector<int32_t> rows;
+  for (int32_t r = 0; r < n_rows; ++r)
+    if (evicted[(size_t)r]) rows.push_back(r);
+  if (tables_dev && !rows.empty()) {
+    // Every request with a block in a chosen handle goes whole, so clearing their rows leaves no entry
+    // that names a chosen handle.  Then the slices that may still hold old entries are waited for.
+    hipStream_t cs = (hipStream_t)stream_v;
+    st = ensure_remap_stage(p);
+    if (st != VKV_OK) return st;
+    std::copy(rows.begin(), rows.end(), p->remap_stage);
+    auto fail = [&](int code) { p->broken = true; return code; };
+    hipError_t he = hipMemcpyAsync(scratch_dev, p->remap_stage, rows.size() * 4, hipMemcpyHostToDevice, cs);
+    if (he != hipSuccess) return fail(hip_fail(he, "row list upload"));
+    hipLaunchKernelGGL(table_clear_rows_kernel, dim3((unsigned)rows.size()), dim3(256), 0, cs, tables_dev, max_blk,
+                       (const int32_t*)scratch_dev);
+    he = hipGetLastError();
+    if (he != hipSuccess) return fail(hip_fail(he, "table_clear_rows launch"));
+    he = hipStreamSynchronize(cs);
+    if (he != hipSuccess) return fail(hip_fail(he, "hipStreamSynchronize"));
+    if (grace_wait(p, cs, (hipStream_t)decode_stream_v) != VKV_OK) return fail(VKV_E_HIP);
+  }
+  list_invalidated(p, chosen, tables, n_rows, max_blk, inv_row_out, inv_col_out, inv_block_out);
+  // blocks the survivors still name stay live whatever row else named them
+  std::vector<uint8_t> kept((size_t)nb, 0);
+  for (int32_t r = 0; r < n_rows; ++r) {
+    if (evicted[(size_t)r]) continue;
+    for (int32_t j = 0; j < max_blk; ++j) {
+      const int32_t e = tables[(size_t)r * max_blk + j];
+      if (e >= 0 && e < nb) kept[(size_t)e] = 1;
+    }
+  }
+  for (int32_t r : rows)
+    for (int32_t j = 0; j < max_blk; ++j) {
+      int32_t& e = tables[(size_t)r * max_blk + j];
+      if (e >= 0 && e < nb && !kept[(size_t)e] && p->live[(size_t)e]) { p->live[(size_t)e] = 0; --p->n_live; }
+      e = -1;
+    }
+  for (int32_t i = 0; i < k; ++i) {
+    const int32_t h = handles_out[i];
+    for (int32_t b = h * bph; b < (h + 1) * bph; ++b)
+      if (p->live[(size_t)b]) { p->live[(size_t)b] = 0; --p->n_live; }
+    p->released.emplace_back(h * bph, (h + 1) * bph, tables_dev != nullptr || rows.empty());
+  }
+  if (evicted_rows_out) std::copy(rows.begin(), rows.end(), evicted_rows_out);
+  info->mode = 1;
+  info->n_handles = k;
+  info->n_evicted = (int32_t)rows.size();
+  info->total_cost = total;
+  return VKV_OK;
+}
+
+int kv_reclaim_or_evict(vkv_pool* p, int32_t lo, int32_t hi, int32_t* tables_dev, int32_t* tables, int32_t n_rows,
+                        int32_t max_blk, const int64_t* cost, uint64_t chunk_bytes, uint64_t rate_cap, void* copy_stream,
+                        void* decode_stream, int32_t* remap_dev, uint32_t flags, int32_t* handles_out,
+                        int32_t* evicted_rows_out, int32_t* inv_row_out, int32_t* inv_col_out, int32_t* inv_block_out,
+                        int32_t cap, vkv_evict_info* info, vkv_reclaim_stats* stats) {
+  if (!p || !info || bad_tables(n_rows, max_blk, tables) || !tables_dev) {
+    set_error("kv_reclaim_or_evict: bad argument");
+    return VKV_E_INVAL;
+  }
+  *info = vkv_evict_info{};
+  int st = kv_reclaim_range(p, lo, hi, tables_dev, (int64_t)n_rows * max_blk, chunk_bytes, rate_cap, copy_stream,
+                            decode_stream, remap_dev, flags, stats);
+  if (st == VKV_OK) {
+    // the host copy of the tables follows the device's: the remap of this call is in the pinned staging
+    // buffer (the upload has finished unless the call was asynchronous, and the host wrote it anyway)
+    const int32_t nb = p->cfg.num_blocks;
+    for (int64_t i = 0; i < (int64_t)n_rows * max_blk; ++i)
+      if (tables[i] >= 0 && tables[i] < nb) tables[i] = p->remap_stage[tables[i]];
+    return VKV_OK;
+  }
+  if (st != VKV_E_NOSPACE) return st;
+  const int32_t k = (hi - lo) / p->cfg.blocks_per_handle;
+  return kv_evict_handles(p, k, tables, n_rows, max_blk, cost, tables_dev, remap_dev, copy_stream, decode_stream,
+                          handles_out, evicted_rows_out, inv_row_out, inv_col_out, inv_block_out, cap, info);
 }
 
 // ---- MIAD headroom ----------------------------------------------------------------------

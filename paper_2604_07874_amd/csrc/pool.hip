@@ -191,17 +191,26 @@ int kv_pool_free(vkv_pool* p, const int32_t* ids, int32_t n) {
 
 int kv_pool_return_range(vkv_pool* p, int32_t lo, int32_t hi) {
   if (!p) { set_error("kv_pool_return_range: null pool"); return VKV_E_INVAL; }
+  const int32_t bph = p->cfg.blocks_per_handle;
+  if (lo < 0 || hi > p->cfg.num_blocks || lo >= hi || lo % bph || hi % bph) {
+    set_error("kv_pool_return_range: [%d,%d) must be non-empty, inside the pool and a multiple of %d blocks", lo, hi, bph);
+    return VKV_E_INVAL;
+  }
   for (size_t i = 0; i < p->released.size(); ++i) {
-    if (p->released[i].first == lo && p->released[i].second == hi) {
-      if (p->arena && !arena_range_mapped(p->arena, lo / p->cfg.blocks_per_handle, hi / p->cfg.blocks_per_handle)) {
+    const vkv_pool::Range r = p->released[i];
+    if (r.first <= lo && hi <= r.second) {
+      if (p->arena && !arena_range_mapped(p->arena, lo / bph, hi / bph)) {
         set_error("kv_pool_return_range: handles of [%d,%d) are unmapped; kv_arena_restore first", lo, hi);
         return VKV_E_STATE;
       }
+      // what is left of the range on either side stays handed over
       p->released.erase(p->released.begin() + (long)i);
+      if (hi < r.second) p->released.insert(p->released.begin() + (long)i, vkv_pool::Range(hi, r.second, r.clean));
+      if (r.first < lo) p->released.insert(p->released.begin() + (long)i, vkv_pool::Range(r.first, lo, r.clean));
       return VKV_OK;
     }
   }
-  set_error("kv_pool_return_range: [%d,%d) is not a handed-over range", lo, hi);
+  set_error("kv_pool_return_range: [%d,%d) does not lie inside one handed-over range", lo, hi);
   return VKV_E_INVAL;
 }
 

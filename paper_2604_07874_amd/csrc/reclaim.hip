@@ -102,14 +102,27 @@ int plan_relocation(const vkv_pool* p, int32_t lo, int32_t hi, std::vector<int32
   return VKV_OK;
 }
 
-static int launch_rewrite(vkv_pool* p, int32_t* tables, int64_t n, const int32_t* remap, int32_t nb,
-                          hipStream_t st) {
+int launch_rewrite(vkv_pool* p, int32_t* tables, int64_t n, const int32_t* remap, int32_t nb, hipStream_t st) {
   if (n == 0) return VKV_OK;
-  vkv_pool none;
+  static vkv_pool none;   // timing records need a pool; a launch without one records nothing
   ProfScope prof(p ? p : &none, VKV_PROF_REWRITE, 0, st);
   int64_t blocks = std::min<int64_t>((n + 255) / 256, 2048);
   hipLaunchKernelGGL(block_table_rewrite_kernel, dim3((unsigned)blocks), dim3(256), 0, st, tables, n, remap, nb);
   VKV_HIP(hipGetLastError());
+  return VKV_OK;
+}
+
+int grace_wait(vkv_pool* p, hipStream_t cs, hipStream_t ds) {
+  if (ds != cs) {
+    // slices enqueued before the rewrite finished may hold old entries (NULL is the default stream)
+    VKV_HIP(hipEventRecord(p->grace_ev, ds));
+    VKV_HIP(hipEventSynchronize(p->grace_ev));
+  }
+  if (p->aux_stream && p->aux_stream != cs) {
+    // slices the scheduler sent to the pool's second stream are in the same position
+    VKV_HIP(hipEventRecord(p->grace_ev, p->aux_stream));
+    VKV_HIP(hipEventSynchronize(p->grace_ev));
+  }
   return VKV_OK;
 }
 
@@ -211,20 +224,7 @@ int kv_reclaim_range(vkv_pool* p, int32_t lo, int32_t hi, int32_t* tables, int64
     he = hipStreamSynchronize(cs);
     if (he != hipSuccess) return fail(hip_fail(he, "hipStreamSynchronize"));
     p->remap_inflight = false;
-    if (ds && ds != cs) {
-      // grace period: slices enqueued before the rewrite finished may hold old entries
-      he = hipEventRecord(p->grace_ev, ds);
-      if (he != hipSuccess) return fail(hip_fail(he, "hipEventRecord"));
-      he = hipEventSynchronize(p->grace_ev);
-      if (he != hipSuccess) return fail(hip_fail(he, "hipEventSynchronize"));
-      if (p->aux_stream) {
-        // slices the scheduler sent to the pool's second stream are in the same position
-        he = hipEventRecord(p->grace_ev, p->aux_stream);
-        if (he != hipSuccess) return fail(hip_fail(he, "hipEventRecord"));
-        he = hipEventSynchronize(p->grace_ev);
-        if (he != hipSuccess) return fail(hip_fail(he, "hipEventSynchronize"));
-      }
-    }
+    if (!(flags & VKV_RECLAIM_NO_GRACE) && grace_wait(p, cs, ds) != VKV_OK) return fail(VKV_E_HIP);
   }
 
   for (size_t i = 0; i < src.size(); ++i) {

@@ -75,7 +75,15 @@ struct vkv_pool {
 
   // occupancy
   std::vector<uint8_t> live;
-  std::vector<std::pair<int32_t, int32_t>> released;   // handed-over ranges [lo,hi)
+  // handed-over ranges [first, second).  `clean` = every device block table the library was shown has
+  // been rewritten and every slice that could hold an old entry has finished: only then may the
+  // range's memory be unmapped.
+  struct Range {
+    int32_t first, second;
+    bool clean;
+    Range(int32_t a, int32_t b, bool c = true) : first(a), second(b), clean(c) {}
+  };
+  std::vector<Range> released;
   int64_t n_live = 0;
 
   // attention plan (host)
@@ -191,6 +199,14 @@ int run_slices(vkv_pool* p, int32_t* cursor, int32_t n_slices, int32_t max_infli
                const std::function<int(int32_t, hipStream_t)>& launch, int32_t n_tail,
                const std::function<int(int32_t)>& tail, bool launches_report);
 int ensure_progress_words(vkv_pool* p);
+
+// Algorithm 1 on the host tables; evicted[r] != 0 for the requests that go.  See kv_select_handles.
+int select_handles_impl(const vkv_pool* p, const int32_t* tables, int32_t n_rows, int32_t max_blk, const int64_t* cost,
+                        int32_t k, int32_t* handles_out, std::vector<uint8_t>& evicted, int64_t* total_out, const char* who);
+// Waits until work enqueued so far on `ds` (if it differs from `cs`) and on the pool's second stream
+// has finished: slices launched before a table rewrite may still hold old entries.
+int grace_wait(vkv_pool* p, hipStream_t cs, hipStream_t ds);
+int launch_rewrite(vkv_pool* p, int32_t* tables, int64_t n, const int32_t* remap, int32_t nb, hipStream_t st);
 
 // Host-side relocation plan; see kv_reclaim_plan.
 int plan_relocation(const vkv_pool* p, int32_t lo, int32_t hi,

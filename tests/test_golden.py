@@ -273,3 +273,30 @@ def test_eviction_examples_oracle():
     st, mode, payload = orc.reclaim_or_evict(*nxt["range"], roe["cost"])
     assert (st, mode) == (R.OK, nxt["mode"])
     assert [[int(a), int(b)] for a, b in zip(payload[0], payload[1])] == nxt["moves"]
+
+
+def test_eviction_examples_library():
+    vkv = _library()
+    ex = load("eviction_examples.json")
+    nb, bph = ex["num_blocks"], ex["blocks_per_handle"]
+
+    def make(case):
+        p = vkv.kv_pool_init(1, 8, 8, 64, nb, bph)
+        vkv.kv_pool_adopt(p, np.flatnonzero(np.array(case["live"])).astype(np.int32))
+        return p, np.array(case["tables"], dtype=np.int32), np.array(case["cost"], dtype=np.int64)
+
+    for case in ex["cases"]:
+        p, tables, cost = make(case)
+        try:
+            fifo = [h for h in range(nb // bph)][:case["k"]]
+            ev, total = vkv.kv_handles_cost(p, tables, cost, fifo)
+            assert (ev.tolist(), total) == (case["fifo"]["evicted"], case["fifo"]["total"])
+            info, handles, evicted, (rows, cols, blks) = vkv.kv_evict_handles(p, case["k"], tables, cost)
+            assert (info.mode, info.n_handles, info.total_cost) == (1, case["k"], case["total"]), case["name"]
+            assert handles.tolist() == case["handles"] and evicted.tolist() == case["evicted"], case["name"]
+            assert [list(x) for x in zip(rows.tolist(), cols.tolist(), blks.tolist())] == case["invalidated"], case["name"]
+            assert tables.tolist() == case["tables_after"], case["name"]
+            live, ranges = vkv.kv_pool_state(p, nb)
+            assert live.tolist() == case["live_after"] and [list(r) for r in ranges] == case["released_after"], case["name"]
+        finally:
+            vkv.kv_pool_destroy(p)

@@ -166,6 +166,92 @@ def test_eviction_makes_room_for_a_relocation_that_did_not_fit(vkv):
     vkv.kv_pool_destroy(p)
 
 
+@pytest.mark.parametrize("name,seed,k", [("tiny", 0, 3), ("tiny", 7, 10), ("llama8b_small", 1, 5), ("stress_small", 2, 4)])
+def test_evict_handles_matches_the_oracle(vkv, name, seed, k):
+    """kv_evict_handles on host tables (no device tables given) against the oracle's eviction, state for state."""
+    from oracle import reclaim as R
+    from oracle.policy import fifo_handles, handle_requests
+    wl = synth.workload(name, shared_prefix_blocks=3 if name != "tiny" else 0)
+    st = synth.build_state(wl, seed, materialize_pool=False)
+    g = wl.geom
+    p = vkv.kv_pool_init(g.num_layers, g.num_q_heads, g.num_kv_heads, g.head_dim, g.num_blocks, g.blocks_per_handle)
+    vkv.kv_pool_adopt(p, np.flatnonzero(st.live).astype(np.int32))
+    n_rows = st.tables.shape[0]
+    cost = np.array([int((st.tables[r] >= 0).sum()) * 16 for r in range(n_rows)], dtype=np.int64)
+    orc = R.ReclaimOracle(g.num_blocks, g.blocks_per_handle, st.live, st.tables, None)
+    tables = st.tables.copy()
+    # the comparison policy: the first k handles
+    reqs = handle_requests(tables, g.num_blocks, g.blocks_per_handle)
+    fh, fe, ft = fifo_handles(k, reqs, cost.tolist())
+    ev, total = vkv.kv_handles_cost(p, tables, cost, fh)
+    assert ev.tolist() == sorted(fe) and total == ft
+    for round_ in range(2):                       # twice: the second time with handles already handed over
+        status, handles, evicted, inv, total = orc.evict(k, cost.tolist())
+        assert status == R.OK
+        info, h, ev, (rows, cols, blks) = vkv.kv_evict_handles(p, k, tables, cost)
+        assert h.tolist() == handles and ev.tolist() == evicted and info.total_cost == total
+        assert list(zip(rows.tolist(), cols.tolist(), blks.tolist())) == inv
+        assert np.array_equal(tables, orc.tables)
+        live, ranges = vkv.kv_pool_state(p, g.num_blocks, max_ranges=256)
+        assert np.array_equal(live, orc.live) and ranges == orc.released
+        vkv.kv_pool_check_tables(p, tables)
+    # too small an output: refused whole, the number needed is reported
+    snap, state = tables.copy(), vkv.kv_pool_state(p, g.num_blocks, max_ranges=256)
+    try:
+        info, _, _, _ = vkv.kv_evict_handles(p, 2, tables, cost, cap=0)
+        assert info.n_invalidated == 0              # the two cheapest handles left were named by nobody
+    except vkv.VkvError as e:
+        assert e.code == vkv.VKV_E_NOSPACE and np.array_equal(tables, snap)
+        after = vkv.kv_pool_state(p, g.num_blocks, max_ranges=256)
+        assert np.array_equal(after[0], state[0]) and after[1] == state[1]
+    vkv.kv_pool_destroy(p)
+
+
+def test_reclaim_or_evict_and_partial_return_on_the_host_side(vkv):
+    """Relocation that does not fit turns into an eviction (the planning part, no device work), and a
+    handed-over range can be given back handle by handle."""
+    from oracle import reclaim as R
+    wl = synth.workload("tiny", occupancy=1.0)
+    st = synth.build_state(wl, 3, materialize_pool=False)
+    g = wl.geom
+    p = vkv.kv_pool_init(g.num_layers, g.num_q_heads, g.num_kv_heads, g.head_dim, g.num_blocks, g.blocks_per_handle)
+    vkv.kv_pool_adopt(p, np.flatnonzero(st.live).astype(np.int32))
+    lo, hi = wl.reclaim_range
+    with pytest.raises(vkv.VkvError) as ei:
+        vkv.kv_reclaim_plan(p, lo, hi, g.num_blocks)
+    assert ei.value.code == vkv.VKV_E_NOSPACE
+    cost = np.array([int((st.tables[r] >= 0).sum()) * 16 for r in range(st.tables.shape[0])], dtype=np.int64)
+    orc = R.ReclaimOracle(g.num_blocks, g.blocks_per_handle, st.live, st.tables, None)
+    k = (hi - lo) // g.blocks_per_handle
+    status, mode, payload = orc.reclaim_or_evict(lo, hi, cost.tolist())
+    assert (status, mode) == (R.OK, 1)
+    tables = st.tables.copy()
+    info, h, ev, _ = vkv.kv_evict_handles(p, k, tables, cost)
+    assert h.tolist() == payload[0] and ev.tolist() == payload[1] and np.array_equal(tables, orc.tables)
+    # the online tenant gives the handles back one at a time, from the middle of a merged picture too
+    bph = g.blocks_per_handle
+    first = int(h[0])
+    assert orc.return_range(first * bph, (first + 1) * bph) == R.OK
+    vkv.kv_pool_return_range(p, first * bph, (first + 1) * bph)
+    live, ranges = vkv.kv_pool_state(p, g.num_blocks, max_ranges=256)
+    assert ranges == orc.released and np.array_equal(live, orc.live)
+    with pytest.raises(vkv.VkvError):
+        vkv.kv_pool_return_range(p, first * bph, (first + 1) * bph)
+    vkv.kv_pool_destroy(p)
+    # partial return of one relocated range
+    p = vkv.kv_pool_init(1, 8, 8, 64, 32, 4)
+    orc = R.ReclaimOracle(32, 4, [0] * 32, [[-1]], None)
+    vkv.kv_invalidate_handles(p, [2, 3, 4, 5], np.array([[-1]], dtype=np.int32))
+    for lo_, hi_, ok in ((6, 10, False), (9, 12, False), (20, 24, True), (12, 16, True), (8, 12, True), (8, 12, False)):
+        if ok:
+            vkv.kv_pool_return_range(p, lo_, hi_)
+        else:
+            with pytest.raises(vkv.VkvError):
+                vkv.kv_pool_return_range(p, lo_, hi_)
+    assert vkv.kv_pool_state(p, 32)[1] == [(16, 20)]
+    vkv.kv_pool_destroy(p)
+
+
 # ------------------------------------------------------------------ MIAD
 MIAD_KW = dict(h_init=4, h_min=2, h_max=64, alpha=1.5, pressure_frac=0.9, t_init=1.0, t_min=0.25, t_max=30.0,
                t_up=2.0, t_down=0.25, window_s=20.0, target_rate=0.1)

@@ -101,7 +101,9 @@ def parse_args():
                     help="extra leg: this many online bursts (yield, reclaim, hold, return) at exponential "
                          "inter-arrival times while decode runs continuously (default: 25 for the stress workload)")
     ap.add_argument("--burst-mean-s", type=float, default=0.2)
-    ap.add_argument("--burst-hold-ms", type=float, default=20.0)
+    ap.add_argument("--burst-hold-ms", type=float, default=20.0, help="mean time a burst keeps its memory")
+    ap.add_argument("--burst-target-rate", type=float, default=4.0,
+                    help="pressure events per second the MIAD controller is asked to stay under")
     ap.add_argument("--prefill-leg", dest="prefill_leg", action="store_true", default=None,
                     help="extra leg: causal prefill of the newest --prefill-tokens tokens of every sequence "
                          "(default: on for the llama8b workload)")
@@ -563,23 +565,47 @@ def run_workload(name, args, workers):
 
 def burst_leg(vkv, args, wl, pool, pool_t, arena, st, q_all, tables, tables0, ws, out, remap, lo, hi, rc_chunk,
               src_ids, dst_ids, decode_bytes_layer, moved_bytes, n_bursts):
-    """Online bursts against a continuous offline decode loop.  Each burst: yield request -> offline
-    compute off the GPU -> the top range emptied and handed over -> the online tenant holds it ->
-    range returned, offline resumes (its KV "grows back": the bookkeeping is rewound; the sources
-    were left intact by the copy)."""
+    """Online bursts against a continuous offline decode loop, with the online tenant's headroom kept by
+    the MIAD controller (Section 5): bursts of 16 GiB-style demand arrive at exponential gaps and last
+    an exponential time; at every arrival, departure and tick the controller sees the handles in use.
+    A pressure event (use >= 90 % of the headroom) grows the headroom: offline compute yields, the
+    highest run of handles still with the offline job is emptied by relocation or, when no room is
+    left, the handles Algorithm 1 picks are evicted, and offline resumes.  Without pressure the
+    controller gives one handle back per interval; the offline job moves back into it (the moves
+    out of that handle are undone in the block tables; the copy had left the sources intact)."""
     import torch
     g = wl.geom
-    L = g.num_layers
+    L, S = g.num_layers, wl.num_seqs
     dev = pool_t.device
-    progress(f"burst leg: {n_bursts} bursts")
+    bph, nb = g.blocks_per_handle, g.num_blocks
+    n_handles = nb // bph
+    burst_handles = (hi - lo) // bph
+    progress(f"burst leg: {n_bursts} bursts of {burst_handles} handles, headroom by the MIAD controller")
     brng = np.random.default_rng(args.seed + 1)
     arrivals = np.cumsum(brng.exponential(args.burst_mean_s, size=n_bursts))
+    holds = brng.exponential(args.burst_hold_ms * 1e-3, size=n_bursts)
+    miad_cfg = dict(h_init=burst_handles + burst_handles // 8, h_min=max(1, burst_handles // 8),
+                    h_max=min(n_handles // 2, 3 * burst_handles), alpha=1.25, pressure_frac=0.9,
+                    t_init=0.004, t_min=0.001, t_max=0.25, t_up=2.0, t_down=0.001, window_s=2.0,
+                    target_rate=float(args.burst_target_rate))
+    miad = vkv.kv_miad_init(**miad_cfg)
     decode_stream, copy_stream = torch.cuda.Stream(), torch.cuda.Stream()
     torch.cuda.synchronize()
     stop = threading.Event()
     cv = threading.Condition()
-    gate = {"want_pause": False, "paused": False}    # both only change under cv
+    gate = {"want_pause": False, "paused": False, "restart_layer": False}    # only change under cv
     layers_done = [0]
+    ctx = st.ctx_len.copy()
+    tables_host = st.tables.copy()
+    cost = np.array([int((tables_host[r] >= 0).sum()) * 16 for r in range(tables_host.shape[0])], dtype=np.int64)
+    cost[:S] = ctx
+    plan_box = [vkv.kv_attn_plan(pool, ctx, args.slice_bytes or wl.slice_bytes, args.chunk_tokens or wl.chunk_tokens)]
+    vkv.kv_attn_bind(pool, ws, decode_stream)
+    vkv.kv_attn_run_layer(pool, 0, 0, q_all[0], tables, ws, out[0], max_inflight=args.max_inflight, stream=decode_stream)
+    decode_stream.synchronize()
+    before = out[0].clone()
+    bytes_layer = [int(plan_box[0].kv_bytes_per_layer)]
+    decoded_bytes = [0]
 
     def offline():
         layer, cur = 0, 0
@@ -590,48 +616,29 @@ def burst_leg(vkv, args, wl, pool, pool_t, arena, st, q_all, tables, tables0, ws
                     cv.notify_all()                # returns only after its launches have drained
                     cv.wait(0.05)
                 gate["paused"] = False
+                if gate["restart_layer"]:          # the batch was planned anew while we were off the GPU
+                    gate["restart_layer"] = False
+                    cur = 0
+            if plan_box[0].n_slices == 0:
+                time.sleep(0.001)
+                continue
             s_, cur = vkv.kv_attn_run_layer(pool, layer, cur, q_all[layer], tables, ws, out[layer],
                                             max_inflight=args.max_inflight, stream=decode_stream)
             if s_ != vkv.VKV_YIELDED:
                 layers_done[0] += 1
+                decoded_bytes[0] += bytes_layer[0]
                 layer, cur = (layer + 1) % L, 0
         decode_stream.synchronize()
 
-    blocks_v = pool_t.view(g.num_blocks, g.block_elems)
-    src_dev = torch.from_numpy(src_ids).to(dev).long()
-    dst_dev = torch.from_numpy(dst_ids).to(dev).long()
-    unmap_ms, map_ms = [], []
+    reserved = np.zeros(n_handles, dtype=bool)      # handles with the online tenant
+    units = []                                      # handed-over handles, newest last: (handle, src ids, dst ids)
+    stats = {"grow_events": 0, "relocations": 0, "evictions": 0, "evicted_requests": 0, "evicted_cost": 0,
+             "fifo_cost": 0, "moved_bytes": 0, "released_handles": 0}
+    grow_ms, idle_ms, paused_s = [], [], [0.0]
+    reloc_ms, evict_ms, reloc_handles, evict_handles, all_gone = [], [], [], [], []
+    ident = torch.arange(nb, dtype=torch.int32, device=dev)
 
-    def give_back(unmapped=False):
-        if unmapped:
-            t_m = time.perf_counter()
-            vkv.kv_arena_restore(arena, pool, lo, hi)
-            map_ms.append((time.perf_counter() - t_m) * 1e3)
-        vkv.kv_pool_return_range(pool, lo, hi)
-        vkv.kv_pool_free(pool, dst_ids)
-        vkv.kv_pool_adopt(pool, src_ids)
-        if unmapped:
-            # the range came back with fresh memory: the offline tenant's blocks move back in
-            with torch.cuda.stream(copy_stream):
-                for i in range(0, len(src_ids), 1024):
-                    blocks_v[src_dev[i:i + 1024]] = blocks_v[dst_dev[i:i + 1024]]
-        with torch.cuda.stream(copy_stream):
-            tables.copy_(tables0)
-        copy_stream.synchronize()
-
-    # one untimed reclamation on the two new streams (their first use creates queues)
-    vkv.kv_reclaim_range(pool, lo, hi, tables, remap, chunk_bytes=rc_chunk, copy_stream=copy_stream,
-                         decode_stream=decode_stream)
-    give_back()
-    th = threading.Thread(target=offline)
-    t_start = time.perf_counter()
-    th.start()
-    to_idle, to_released, paused = [], [], 0.0
-    for a in arrivals:
-        now = time.perf_counter() - t_start
-        if a > now:
-            time.sleep(a - now)
-        t_arr = max(a, now) + t_start     # a burst that finds the previous one in service waits its turn
+    def pause_offline():
         t_req = time.perf_counter()
         with cv:
             gate["want_pause"] = True
@@ -639,48 +646,199 @@ def burst_leg(vkv, args, wl, pool, pool_t, arena, st, q_all, tables, tables0, ws
         with cv:
             while not gate["paused"]:
                 cv.wait()
-        t_idle = time.perf_counter()
-        vkv.kv_reclaim_range(pool, lo, hi, tables, remap, chunk_bytes=rc_chunk, copy_stream=copy_stream,
-                             decode_stream=decode_stream)
-        t_rel = time.perf_counter()      # handed over: a tenant in this process may use the range now
-        if arena is not None:
-            vkv.kv_arena_release(arena, pool, lo, hi)     # the physical memory is the driver's again
-            unmap_ms.append((time.perf_counter() - t_rel) * 1e3)
-        to_idle.append((t_idle - t_req) * 1e3)
-        to_released.append((t_rel - min(t_arr, t_req)) * 1e3)
-        time.sleep(args.burst_hold_ms * 1e-3)
-        give_back(unmapped=arena is not None)
+        return t_req, time.perf_counter()
+
+    def resume_offline(t_req):
         vkv.kv_yield_clear(pool)
-        paused += time.perf_counter() - t_req
+        paused_s[0] += time.perf_counter() - t_req
         with cv:
             gate["want_pause"] = False
             cv.notify_all()
-        if len(to_released) % 10 == 0:
-            progress(f"  burst {len(to_released)} of {n_bursts}")
+
+    def top_run(n):
+        """Highest run of n consecutive handles still with the offline job, as a block range."""
+        run = 0
+        for h in range(n_handles - 1, -1, -1):
+            run = run + 1 if not reserved[h] else 0
+            if run == n:
+                return h * bph, (h + n) * bph
+        return None
+
+    def grow(n, timed=True):
+        rng_ = top_run(n)
+        if rng_ is None:
+            return False
+        rlo, rhi = rng_
+        t_req, t_idle = pause_offline() if timed else (time.perf_counter(),) * 2
+        try:
+            remap_plan = None
+            try:
+                remap_plan, _ = vkv.kv_reclaim_plan(pool, rlo, rhi, nb)
+            except vkv.VkvError as e:
+                if e.code != vkv.VKV_E_NOSPACE:
+                    raise
+                # what first-in-first-out eviction of as many handles would have cost (Section 7.2)
+                fifo = np.flatnonzero(~reserved)[:n].astype(np.int32)
+                stats["fifo_cost"] += vkv.kv_handles_cost(pool, tables_host, cost, fifo)[1]
+            info, rs, handles, evicted, _ = vkv.kv_reclaim_or_evict(
+                pool, rlo, rhi, tables, tables_host, cost, remap, chunk_bytes=rc_chunk, copy_stream=copy_stream,
+                decode_stream=decode_stream)
+            if info.mode == 0:
+                src = np.flatnonzero(remap_plan != np.arange(nb)).astype(np.int32)
+                dst = remap_plan[src].astype(np.int32)
+                for h in range(rhi // bph - 1, rlo // bph - 1, -1):     # top handle first, so that giving back
+                    m = (src // bph) == h                                  # starts at the boundary
+                    units.append((h, src[m], dst[m]))
+                    reserved[h] = True
+                stats["relocations"] += 1
+                stats["moved_bytes"] += int(rs.bytes_moved)
+            else:
+                for h in handles.tolist():
+                    units.append((int(h), None, None))
+                    reserved[int(h)] = True
+                stats["evictions"] += 1
+                stats["evicted_requests"] += int(info.n_evicted)
+                stats["evicted_cost"] += int(info.total_cost)
+                gone = [r for r in evicted.tolist() if r < S]
+                all_gone.extend(gone)
+                if gone:
+                    # the evicted requests leave the batch; the next slices follow a new plan
+                    ctx[gone] = 0
+                    plan_box[0] = vkv.kv_attn_plan(pool, ctx, args.slice_bytes or wl.slice_bytes,
+                                                   args.chunk_tokens or wl.chunk_tokens)
+                    bytes_layer[0] = int(plan_box[0].kv_bytes_per_layer)
+                    vkv.kv_attn_bind(pool, ws, decode_stream)
+                    with cv:
+                        gate["restart_layer"] = True
+            t_done = time.perf_counter()
+            if timed:
+                grow_ms.append((t_done - t_req) * 1e3)
+                idle_ms.append((t_idle - t_req) * 1e3)
+                stats["grow_events"] += 1
+                (evict_ms if info.mode else reloc_ms).append((t_done - t_idle) * 1e3)
+                (evict_handles if info.mode else reloc_handles).append(n)
+            if arena is not None:
+                for h, _, _ in units[-n:]:
+                    vkv.kv_arena_release(arena, pool, h * bph, (h + 1) * bph)
+        finally:
+            if timed:
+                resume_offline(t_req)
+        return True
+
+    def release_one():
+        """The newest handed-over handle goes back; the offline job's blocks return to it."""
+        if not units:
+            return
+        h, src, dst = units.pop()
+        if arena is not None:
+            vkv.kv_arena_restore(arena, pool, h * bph, (h + 1) * bph)
+        vkv.kv_pool_return_range(pool, h * bph, (h + 1) * bph)
+        reserved[h] = False
+        stats["released_handles"] += 1
+        if src is not None and len(src):
+            # a request evicted since then took its blocks with it: nothing of it moves back
+            kept = np.isin(dst, tables_host[tables_host >= 0])
+            src, dst = src[kept], dst[kept]
+        if src is not None and len(src):
+            # undo the moves out of this handle: the sources were left intact, so only bookkeeping and tables change.
+            # Slices in flight may read either copy (same bytes); the old destinations are freed, not overwritten.
+            vkv.kv_pool_free(pool, dst)
+            vkv.kv_pool_adopt(pool, src)
+            inv = ident.clone()
+            inv[torch.from_numpy(dst).to(dev).long()] = torch.from_numpy(src).to(dev)
+            with torch.cuda.stream(copy_stream):
+                vkv.block_table_rewrite(tables, inv, nb, stream=copy_stream)
+            back = np.arange(nb, dtype=np.int32)
+            back[dst] = src
+            used = tables_host >= 0
+            tables_host[used] = back[tables_host[used]]
+            copy_stream.synchronize()
+
+    # the initial headroom is taken before anything is timed (also creates the queues of the two new streams)
+    h0 = vkv.kv_miad_observe(miad, 0.0, 0)[0]
+    grow(h0, timed=False)
+    th = threading.Thread(target=offline)
+    t_start = time.perf_counter()
+    th.start()
+    timeline = sorted([(float(a), +1) for a in arrivals] + [(float(a + h), -1) for a, h in zip(arrivals, holds)])
+    tick_s = 0.002
+    active, k_ev, n_pressure, headroom_trace = 0, 0, 0, []
+    served_late = 0
+    t_end = timeline[-1][0] + 0.05
+    while True:
+        now = time.perf_counter() - t_start
+        if now >= t_end:
+            break
+        nxt = timeline[k_ev][0] if k_ev < len(timeline) else t_end
+        wait = min(nxt, now + tick_s) - now
+        if wait > 0:
+            time.sleep(wait)
+        now = time.perf_counter() - t_start
+        while k_ev < len(timeline) and timeline[k_ev][0] <= now:
+            active += timeline[k_ev][1]
+            k_ev += 1
+        used_h = active * burst_handles
+        for _ in range(32):                       # the controller until it has nothing more to ask for
+            H, grow_by, release, event, T = vkv.kv_miad_observe(miad, time.perf_counter() - t_start, used_h)
+            n_pressure += event
+            if grow_by > 0:
+                if not grow(grow_by):
+                    break
+                continue                          # pressure may persist: the next observation decides
+            if release:
+                release_one()
+            break
+        headroom_trace.append(H)
+        if used_h > H:
+            served_late += 1
     stop.set()
     th.join()
     torch.cuda.synchronize()
-    vkv.kv_attn_bind(pool, ws, torch.cuda.current_stream())     # the loop may have stopped inside a layer
-    torch.cuda.synchronize()
     total_s = time.perf_counter() - t_start
+    # everything goes back, newest first, so that the pool ends as it began (bar the evicted requests)
+    while units:
+        release_one()
+    vkv.kv_miad_destroy(miad)
+    # the evicted requests come back for the legs that follow: their blocks were freed, never overwritten
+    live_now, _ = vkv.kv_pool_state(pool, nb)
+    vkv.kv_pool_adopt(pool, np.flatnonzero(st.live.astype(bool) & ~live_now.astype(bool)).astype(np.int32))
+    tables.copy_(tables0)
+    vkv.kv_attn_plan(pool, st.ctx_len, args.slice_bytes or wl.slice_bytes, args.chunk_tokens or wl.chunk_tokens)
+    vkv.kv_attn_bind(pool, ws, torch.cuda.current_stream())
+    vkv.kv_attn_run_layer(pool, 0, 0, q_all[0], tables, ws, out[0], max_inflight=args.max_inflight,
+                          stream=torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    # the requests that stayed compute the same bits as before the bursts; the evicted ones lost their KV for good
+    stayed = torch.ones(S, dtype=torch.bool, device=dev)
+    if all_gone:
+        stayed[torch.tensor(sorted(set(all_gone)), device=dev)] = False
+    same_bits = bool(torch.equal(out[0][stayed].view(torch.int32), before[stayed].view(torch.int32)))
+    run_s = max(1e-9, total_s - paused_s[0])
     res = {
-        "bursts": int(n_bursts), "burst_mean_interarrival_s": args.burst_mean_s,
-        "burst_hold_ms": args.burst_hold_ms, "burst_run_s": round(total_s, 2),
-        "burst_reclaimed_bytes": int((hi - lo) * g.block_bytes), "burst_moved_bytes": int(moved_bytes),
-        "burst_yield_to_idle_ms_p50": round(percentile(to_idle, 50), 3),
-        "burst_yield_to_idle_ms_p99": round(percentile(to_idle, 99), 3),
-        "burst_arrival_to_released_ms_p50": round(percentile(to_released, 50), 3),
-        "burst_arrival_to_released_ms_p99": round(percentile(to_released, 99), 3),
-        "burst_arrival_to_released_ms_max": round(max(to_released), 3),
-        "burst_offline_paused_frac": round(paused / total_s, 4),
-        "burst_decode_GBps_whole_run": round(layers_done[0] * decode_bytes_layer / total_s / 1e9, 1),
-        "burst_decode_GBps_while_running": round(layers_done[0] * decode_bytes_layer / (total_s - paused) / 1e9, 1),
+        "bursts": int(n_bursts), "burst_handles": int(burst_handles), "burst_bytes": int((hi - lo) * g.block_bytes),
+        "burst_mean_interarrival_s": args.burst_mean_s, "burst_mean_hold_ms": args.burst_hold_ms,
+        "burst_run_s": round(total_s, 2), "burst_survivors_bits_unchanged_afterwards": same_bits,
+        "miad": {**miad_cfg, "pressure_events": int(n_pressure),
+                 "pressure_events_per_s": round(n_pressure / total_s, 3),
+                 "headroom_handles_mean": round(float(np.mean(headroom_trace)), 1) if headroom_trace else None,
+                 "headroom_handles_max": int(max(headroom_trace)) if headroom_trace else None,
+                 "observations_with_use_above_headroom": int(served_late)},
+        "burst_grow_events": stats["grow_events"], "burst_relocations": stats["relocations"],
+        "burst_evictions": stats["evictions"], "burst_evicted_requests": stats["evicted_requests"],
+        "burst_evicted_cost_tokens": stats["evicted_cost"], "burst_fifo_cost_tokens": stats["fifo_cost"],
+        "burst_moved_bytes_total": stats["moved_bytes"], "burst_released_handles": stats["released_handles"],
+        "burst_yield_to_idle_ms_p50": round(percentile(idle_ms, 50), 3) if idle_ms else None,
+        "burst_yield_to_idle_ms_p99": round(percentile(idle_ms, 99), 3) if idle_ms else None,
+        "burst_request_to_handed_over_ms_p50": round(percentile(grow_ms, 50), 3) if grow_ms else None,
+        "burst_request_to_handed_over_ms_p99": round(percentile(grow_ms, 99), 3) if grow_ms else None,
+        "burst_request_to_handed_over_ms_max": round(max(grow_ms), 3) if grow_ms else None,
+        "burst_relocation_ms_max": round(max(reloc_ms), 3) if reloc_ms else None,
+        "burst_relocation_handles_max": int(max(reloc_handles)) if reloc_handles else None,
+        "burst_eviction_ms": [round(x, 3) for x in evict_ms], "burst_eviction_handles": [int(x) for x in evict_handles],
+        "burst_offline_paused_frac": round(paused_s[0] / total_s, 4),
+        "burst_decode_GBps_whole_run": round(decoded_bytes[0] / total_s / 1e9, 1),
+        "burst_decode_GBps_while_running": round(decoded_bytes[0] / run_s / 1e9, 1),
     }
-    if arena is not None:
-        res.update({"burst_unmap_ms_p50": round(percentile(unmap_ms, 50), 3),
-                    "burst_unmap_ms_p99": round(percentile(unmap_ms, 99), 3),
-                    "burst_map_ms_p50": round(percentile(map_ms, 50), 3),
-                    "burst_map_ms_p99": round(percentile(map_ms, 99), 3)})
     return res
 
 

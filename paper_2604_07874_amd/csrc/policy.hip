@@ -61,21 +61,28 @@ int select_handles_impl(const vkv_pool* p, const int32_t* tables, int32_t n_rows
     set_error("%s: %d handles wanted, %d not yet handed over", who, k, n_cand);
     return VKV_E_NOSPACE;
   }
+  // Cost of a handle = summed cost of its requests not yet evicted.  Kept up to date as requests go
+  // (the same integers a fresh sum would give), so that a pick is one pass over the handles.
+  std::vector<std::vector<int32_t>> row_handles((size_t)n_rows);
+  std::vector<int64_t> hcost((size_t)n_handles, 0);
+  for (int32_t h = 0; h < n_handles; ++h)
+    for (int32_t r : reqs[(size_t)h]) {
+      row_handles[(size_t)r].push_back(h);
+      hcost[(size_t)h] += cost[r];
+    }
   int64_t total = 0;
   for (int32_t i = 0; i < k; ++i) {
     int32_t best = -1;
-    int64_t best_cost = 0;
-    for (int32_t h = 0; h < n_handles; ++h) {
-      if (!candidate[(size_t)h]) continue;
-      int64_t c = 0;
-      for (int32_t r : reqs[(size_t)h])
-        if (!evicted[(size_t)r]) c += cost[r];
-      if (best < 0 || c < best_cost) { best = h; best_cost = c; }   // ties: lowest handle index
-    }
+    for (int32_t h = 0; h < n_handles; ++h)
+      if (candidate[(size_t)h] && (best < 0 || hcost[(size_t)h] < hcost[(size_t)best])) best = h;   // ties: lowest index
     handles_out[i] = best;
     candidate[(size_t)best] = 0;
-    total += best_cost;
-    for (int32_t r : reqs[(size_t)best]) evicted[(size_t)r] = 1;
+    total += hcost[(size_t)best];
+    for (int32_t r : reqs[(size_t)best]) {
+      if (evicted[(size_t)r]) continue;
+      evicted[(size_t)r] = 1;
+      for (int32_t h : row_handles[(size_t)r]) hcost[(size_t)h] -= cost[r];
+    }
   }
   if (total_out) *total_out = total;
   return VKV_OK;

@@ -42,7 +42,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 
 
 def library_path() -> str:
-    return os.path.join(_HERE, "libvalvekv.so")
+    """The in-tree library; VALVEKV_LIBRARY names another build of the same sources (the host-sanitizer one)."""
+    return os.environ.get("VALVEKV_LIBRARY") or os.path.join(_HERE, "libvalvekv.so")
 
 
 class VkvError(RuntimeError):

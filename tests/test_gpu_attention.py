@@ -98,6 +98,37 @@ def test_overlapped_slices_keep_stream_order_and_bits():
         c.close()
 
 
+def test_merge_is_repeatable_when_chunks_of_a_sequence_arrive_from_many_launches():
+    """32 chunks per sequence, cut into slices far smaller than a sequence so that the chunks of one
+    (sequence, kv head) finish in different launches running side by side on two streams; whichever
+    workgroup arrives last merges.  Twenty passes must give the bits of the one-launch result."""
+    from gpu_util import DeviceCase
+    wl = synth.workload("offline_batch_small", ctx_dist=("uniform", 3969, 4096))
+    c = DeviceCase(wl, seed=47)
+    try:
+        g, vkv = wl.geom, c.vkv
+        assert int(np.ceil(c.st.ctx_len / 128).min()) == 32
+        q, q_t = c.q_dev(0)
+        one = c.plan(slice_bytes=1 << 40, chunk_tokens=128)
+        assert one.n_slices == 1
+        ref = c.attention(0, q_t)
+        many = c.plan(slice_bytes=1 << 20, chunk_tokens=128)
+        assert many.n_slices >= 64 and many.n_items == one.n_items
+        vkv.kv_sched_set_overlap(c.pool, True)
+        stream = torch.cuda.Stream()
+        out = torch.empty((wl.num_seqs, g.num_q_heads, g.head_dim), dtype=torch.float32, device="cuda:0")
+        for rep in range(20):
+            with torch.cuda.stream(stream):
+                out.fill_(float("nan"))
+                st, cur = vkv.kv_attn_run_layer(c.pool, 0, 0, q_t, c.tables_t, c.ws, out, max_inflight=4, stream=stream)
+            stream.synchronize()
+            assert (st, cur) == (vkv.VKV_OK, many.n_slices)
+            assert np.array_equal(out.cpu().numpy().view(np.uint32), ref.view(np.uint32)), f"pass {rep}"
+        vkv.kv_attn_check(c.pool, c.ws, stream)
+    finally:
+        c.close()
+
+
 def test_hand_derived_exact_cases_through_the_library():
     """The exact-rational cases of tests/golden/attention_exact_cases.json, embedded in head_dim 128
     (extra dimensions zero), through the decode and the prefill kernels: checks the library against

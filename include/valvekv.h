@@ -335,7 +335,8 @@ typedef struct vkv_prefill_plan_info {
  *   - work item = (tile, kv head, chunk), order tile, chunk, kv head;
  *   - a slice is a maximal run of items reading at most slice_bytes of K+V.
  * Query rows are packed: sequence s owns rows sum(q_len[:s]) .. + q_len[s].
- * Errors: VKV_E_INVAL (needs 1 <= q_len <= ctx_len). */
+ * Errors: VKV_E_INVAL (needs 1 <= q_len <= ctx_len; a pool whose head_dim is
+ * not 128 is refused here, before any workspace is sized). */
 int kv_prefill_plan(vkv_pool* pool, const int32_t* ctx_len_host, const int32_t* q_len_host, int32_t num_seqs,
                     uint64_t slice_bytes, int32_t chunk_tokens, vkv_prefill_plan_info* info_out);
 

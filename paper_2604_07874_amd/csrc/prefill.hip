@@ -130,6 +130,11 @@ __global__ __launch_bounds__(256, 2) void paged_prefill_attn_slice_kernel(const 
 
   // this wave's share of a group: rows 4r+kg, r in {r0, r0+1}, of block (wave >> 1)
   const int sb = wave >> 1, r0 = (wave & 1) * 2;
+  // Where this wave's token pair goes inside a lane's 16-byte V operand: rotated by the lane's k-group,
+  // so that the 64 one-dword writes of a wave fall on 64 different dword columns instead of every fourth
+  // one.  The weights are rotated the same way before the p.V products (a sum over tokens does not care
+  // in which order the tokens sit, as long as both operands agree).
+  const int vslot = (wave + kg) & 3;
   struct Rows { u32x4 k[2], v[2]; };
   auto fetch = [&](int grp) -> Rows {
     Rows x;
@@ -172,7 +177,7 @@ __global__ __launch_bounds__(256, 2) void paged_prefill_attn_slice_kernel(const 
 #pragma unroll
     for (int dt = 0; dt < EPL; ++dt) {
       const uint32_t sel = (dt & 1) ? 0x07060302u : 0x05040100u;
-      va_lds[(dt * 64 + lane) * 4 + wave] = __builtin_amdgcn_perm(cur.v[1][dt >> 1], cur.v[0][dt >> 1], sel);
+      va_lds[(dt * 64 + lane) * 4 + vslot] = __builtin_amdgcn_perm(cur.v[1][dt >> 1], cur.v[0][dt >> 1], sel);
     }
     cur = nx1;
     if (grp + 2 < ngroups) nx1 = fetch(grp + 2);
@@ -234,6 +239,14 @@ __global__ __launch_bounds__(256, 2) void paged_prefill_attn_slice_kernel(const 
 #pragma unroll
       for (int i = 0; i < 8; ++i)
         pb[i] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sc[i >> 2][i & 3], p.scale_log2, -m_run[j]));
+      {
+        // token pair w of the weights moves to slot (w + kg) & 3, as in the staged V operand
+        const u32x4 pw = __builtin_bit_cast(u32x4, pb);
+        const bool r1 = kg & 1, r2 = kg & 2;
+        const u32x4 t = {r1 ? pw[3] : pw[0], r1 ? pw[0] : pw[1], r1 ? pw[1] : pw[2], r1 ? pw[2] : pw[3]};
+        const u32x4 u = {r2 ? t[2] : t[0], r2 ? t[3] : t[1], r2 ? t[0] : t[2], r2 ? t[1] : t[3]};
+        pb = __builtin_bit_cast(bf16x8, u);
+      }
       // the row sums come from the matrix unit too (a tile of ones as the "V" operand), so the
       // denominator sums exactly the rounded weights the numerator uses
       accl[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb, accl[j], 0, 0, 0);
@@ -456,6 +469,7 @@ int kv_prefill_plan(vkv_pool* p, const int32_t* ctx, const int32_t* q_len, int32
     return VKV_E_INVAL;
   }
   const int Hkv = p->cfg.num_kv_heads, D = p->cfg.head_dim, B = p->cfg.block_tokens, G = p->G;
+  if (D != 128) { set_error("kv_prefill_plan: prefill supports head_dim 128 only (pool has %d)", D); return VKV_E_INVAL; }
   int gp_shift = 0;
   while ((1 << gp_shift) < G) ++gp_shift;
   const int QP = kTileColumns >> gp_shift;   // positions per tile

@@ -143,6 +143,16 @@ def test_device_entry_points_refuse_a_host_only_pool(vkv):
     vkv.kv_pool_destroy(p)
 
 
+def test_prefill_plan_refuses_head_dim_64(vkv):
+    p = vkv.kv_pool_init(2, 8, 2, 64, 64, 8)
+    try:
+        with pytest.raises(vkv.VkvError) as e:
+            vkv.kv_prefill_plan(p, np.array([40], dtype=np.int32), np.array([8], dtype=np.int32), 1 << 20, 256)
+        assert e.value.code == vkv.VKV_E_INVAL and "head_dim 128" in str(e.value)
+    finally:
+        vkv.kv_pool_destroy(p)
+
+
 def test_prefill_merge_is_cut_into_bounded_steps(vkv):
     """Host only: the merge of split tiles is planned as steps whose size follows slice_bytes, one
     step when nothing is split."""

@@ -132,11 +132,11 @@ WORKLOADS: Dict[str, Workload] = {
                         ("lognormal", 2048, 0.7, 16, 8192), 0.70, 2048, slice_bytes=1 << 30),
     "offline_batch": Workload("offline_batch", _g(8, 32, 8, 128, 327680, 128), 256,
                               ("uniform", 512, 32768), None, 16384, chunk_bytes=64 << 20, rate_cap=20e9,
-                              chunk_tokens=2048),
+                              slice_bytes=1 << 30, chunk_tokens=2048),
     "llama70b_tp8": Workload("llama70b_tp8", _g(80, 8, 1, 128, 104832, 64), 128,
                              ("lognormal", 4096, 0.7, 16, 16384), 0.85, 13120, slice_bytes=1 << 30),
     "stress": Workload("stress", _g(10, 32, 8, 128, 327680, 64), 512,
-                       ("uniform", 256, 16384), 0.90, 26240, chunk_tokens=2048),
+                       ("uniform", 256, 16384), 0.90, 26240, slice_bytes=1 << 30, chunk_tokens=2048),
     # Reduced shapes (same heads, fewer layers / sequences / blocks) that a CPU
     # oracle finishes in seconds yet span several chunks, slices and ragged tails.
     "llama8b_small": Workload("llama8b_small", _g(2, 32, 8, 128, 2048, 32), 8,

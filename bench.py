@@ -386,7 +386,18 @@ def run_workload(name, args, workers):
         cp_b = torch.empty(cp_bytes, dtype=torch.uint8, device=dev)
         copy_ms = timed_ms(lambda i: vkv.kv_probe_copy(cp_b, cp_a, cp_bytes, stream), 4)
         del cp_a, cp_b
+        # what a pair of timing events around one launch reads when the launch itself is next to nothing
+        # (a 64 KiB read): the share of every per-launch figure above that is not the kernel
+        br = []
+        for _ in range(20):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            vkv.kv_probe_read(base_addr, 65536, sink, stream)
+            e1.record(stream)
+            e1.synchronize()
+            br.append(e0.elapsed_time(e1) * 1e3)
         ceilings = {
+            "event_pair_around_64KiB_read_us": round(float(np.median(br)), 2),
             "sequential_read_GBps": round(big / read_big_ms / 1e6, 1), "sequential_read_bytes": int(big),
             "sequential_read_at_launch_size_GBps": round(launch_sized / read_launch_ms / 1e6, 1),
             "launch_size_bytes": int(launch_sized),

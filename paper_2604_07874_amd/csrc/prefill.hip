@@ -185,15 +185,30 @@ __global__ __launch_bounds__(256, 2) void paged_prefill_attn_slice_kernel(const 
     // passed the previous group's barrier since
     __syncthreads();
 
-    // ---- operands shared by this wave's column tiles ----
-    bf16x8 ka[2][KS], va[EPL];
+    // ---- scores of both column tiles first: the second tile's products run in the matrix unit while
+    // the first tile's softmax runs on the vector unit, and the K operands are dead before the V
+    // operands are read ----
     const int trow_lds = 4 * (c16 & 3) + (c16 >> 2);
+    f32x4 sc[kNQ][2];
+    {
+      bf16x8 ka[2][KS];
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+      for (int b = 0; b < 2; ++b)
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
-        ka[b][ks] = __builtin_bit_cast(
-            bf16x8, *reinterpret_cast<const u32x4*>(k_lds + (b * 16 + trow_lds) * RS + (ks * 4 + kg) * 16));
+        for (int ks = 0; ks < KS; ++ks)
+          ka[b][ks] = __builtin_bit_cast(
+              bf16x8, *reinterpret_cast<const u32x4*>(k_lds + (b * 16 + trow_lds) * RS + (ks * 4 + kg) * 16));
+#pragma unroll
+      for (int j = 0; j < kNQ; ++j)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+          sc[j][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks)
+            sc[j][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[b][ks], qb[j][ks], sc[j][b], 0, 0, 0);
+        }
+    }
+    bf16x8 va[EPL];
 #pragma unroll
     for (int dt = 0; dt < EPL; ++dt)
       va[dt] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(&va_lds[(dt * 64 + lane) * 4]));
@@ -201,16 +216,9 @@ __global__ __launch_bounds__(256, 2) void paged_prefill_attn_slice_kernel(const 
     // A group is interior for this wave when every token of it exists and is visible to every column of
     // the wave; only the groups on the causal diagonal and a ragged last group need the mask.
     const bool interior = tok0 + kGroupTokens <= ntok && tok0 + kGroupTokens - 1 <= wave_limit;
+    bf16x8 pbs[kNQ];
 #pragma unroll
     for (int j = 0; j < kNQ; ++j) {
-      f32x4 sc[2];
-#pragma unroll
-      for (int b = 0; b < 2; ++b) {
-        sc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-          sc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[b][ks], qb[j][ks], sc[b], 0, 0, 0);
-      }
       if (!interior) {
         // column = (position cpos[j], head cg[j]); token tok0 + 16b + 4r + kg sits at position tok_base + that
         const int limit = min(pos0 + cpos[j] - tok_base, ntok - 1);   // last visible token index within the item
@@ -218,13 +226,13 @@ __global__ __launch_bounds__(256, 2) void paged_prefill_attn_slice_kernel(const 
         for (int b = 0; b < 2; ++b)
 #pragma unroll
           for (int r = 0; r < 4; ++r)
-            if (tok0 + b * 16 + 4 * r + kg > limit) sc[b][r] = NEG_INF;   // also drops NaN from rows past the end
+            if (tok0 + b * 16 + 4 * r + kg > limit) sc[j][b][r] = NEG_INF;   // also drops NaN from rows past the end
       }
       // The running reference m_run follows the column maximum lazily: it moves only when some score
       // exceeds it by more than kSlack (log2 units), so p stays below 2^kSlack and most groups skip
       // both the cross-lane maximum and the rescaling of the accumulators.
-      const float mx = fmaxf(fmaxf(fmaxf(sc[0][0], sc[0][1]), fmaxf(sc[0][2], sc[0][3])),
-                             fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
+      const float mx = fmaxf(fmaxf(fmaxf(sc[j][0][0], sc[j][0][1]), fmaxf(sc[j][0][2], sc[j][0][3])),
+                             fmaxf(fmaxf(sc[j][1][0], sc[j][1][1]), fmaxf(sc[j][1][2], sc[j][1][3])));
       if (__builtin_amdgcn_ballot_w64(fmaf(mx, p.scale_log2, -kSlack) > m_run[j]) != 0ull) {
         float mc = fmaxf(mx, __shfl_xor(mx, 16));
         mc = fmaxf(mc, __shfl_xor(mc, 32));
@@ -238,21 +246,21 @@ __global__ __launch_bounds__(256, 2) void paged_prefill_attn_slice_kernel(const 
       bf16x8 pb;
 #pragma unroll
       for (int i = 0; i < 8; ++i)
-        pb[i] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sc[i >> 2][i & 3], p.scale_log2, -m_run[j]));
+        pb[i] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sc[j][i >> 2][i & 3], p.scale_log2, -m_run[j]));
       {
         // token pair w of the weights moves to slot (w + kg) & 3, as in the staged V operand
         const u32x4 pw = __builtin_bit_cast(u32x4, pb);
         const bool r1 = kg & 1, r2 = kg & 2;
         const u32x4 t = {r1 ? pw[3] : pw[0], r1 ? pw[0] : pw[1], r1 ? pw[1] : pw[2], r1 ? pw[2] : pw[3]};
         const u32x4 u = {r2 ? t[2] : t[0], r2 ? t[3] : t[1], r2 ? t[0] : t[2], r2 ? t[1] : t[3]};
-        pb = __builtin_bit_cast(bf16x8, u);
+        pbs[j] = __builtin_bit_cast(bf16x8, u);
       }
       // the row sums come from the matrix unit too (a tile of ones as the "V" operand), so the
       // denominator sums exactly the rounded weights the numerator uses
-      accl[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb, accl[j], 0, 0, 0);
+      accl[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pbs[j], accl[j], 0, 0, 0);
 #pragma unroll
       for (int dt = 0; dt < EPL; ++dt)
-        acc[j][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pb, acc[j][dt], 0, 0, 0);
+        acc[j][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pbs[j], acc[j][dt], 0, 0, 0);
     }
   }
 

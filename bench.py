@@ -250,8 +250,8 @@ def run_workload(name, args, workers, headline=True):
     # one-stream pass of their own after the timed steps
     events_in_steps = not overlap
     if events_in_steps:
-        # every eighth launch is bracketed: two event records around a launch cost its neighbours several
-        # microseconds, and the timed steps should run as an untimed caller's would
+        # every eighth launch carries timing events (the dispatch's own start and end: nothing is enqueued
+        # around it), so the timed steps run as an untimed caller's would
         vkv.kv_profile_enable(pool, launches_per_step * (args.steps + 1) + 16)
         vkv.kv_profile_sample(pool, EVENT_STRIDE)
 
@@ -331,9 +331,10 @@ def run_workload(name, args, workers, headline=True):
                 "traffic": None if attn_ratio is None else int(attn_ratio * bytes_per_launch),
                 "avg_launch_us": round(slice_ms_avg * 1e3, 2),
                 "bytes_per_launch": int(bytes_per_launch), "launches": int(len(sl)),
-                "method": (f"HIP events around every {EVENT_STRIDE}th launch inside the timed steps" if events_in_steps else
-                           "HIP events around every 3rd launch in a one-stream pass after the timed steps (the timed "
-                           "steps alternate slices between two streams, where durations are not additive)")}
+                "method": ((f"HIP events carried by every {EVENT_STRIDE}th launch inside the timed steps" if events_in_steps else
+                            "HIP events carried by every 3rd launch in a one-stream pass after the timed steps (the timed "
+                            "steps alternate slices between two streams, where durations are not additive)")
+                           + "; hipExtLaunchKernelGGL start/stop events = the dispatch's own start and end")}
     roofline_reclaim = None
     if len(rl) and int(rl["index"].sum()) > 0:
         n_launches = int(rl["index"].sum())

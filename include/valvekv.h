@@ -524,19 +524,23 @@ int kv_gate_stats(vkv_gate* g, double* max_gap_s_out, int64_t* preemptions_out);
 typedef struct vkv_profile_record {
   int32_t kind;
   int32_t index;
-  float   ms;                 /* device time between events recorded around the launch */
+  float   ms;                 /* device time of the launch (slice kernels: the dispatch's own start to end;
+                                 copy and rewrite: between events recorded around the launches) */
 } vkv_profile_record;
 
-/* With max_records > 0 every kernel launch of this pool is bracketed by two
- * timing events on its stream until max_records launches have been recorded;
- * 0 turns recording off and frees the events.  Used for roofline measurement;
- * the events cost a few microseconds per launch. */
+/* With max_records > 0 every kernel launch of this pool is timed with two
+ * events until max_records launches have been recorded; 0 turns recording off
+ * and frees the events.  Used for roofline measurement.  A slice launch
+ * (decode or prefill) carries its two events itself (hipExtLaunchKernelGGL):
+ * they take the dispatch's start and end, nothing is enqueued between the
+ * kernel and its neighbours, and the figure is the kernel's duration as a
+ * profiler reports it.  Copy and rewrite launches are bracketed by events
+ * recorded on their stream, which adds a few microseconds to the figure. */
 int kv_profile_enable(vkv_pool* pool, int32_t max_records);
 
-/* Brackets only every stride-th slice launch (default 1 = every launch; copy and
- * rewrite launches are always bracketed): the two events
- * around a launch keep its neighbours from following it directly, so sampling
- * keeps a timed run close to an untimed one.  Errors: VKV_E_INVAL. */
+/* Times only every stride-th slice launch (default 1 = every launch; copy and
+ * rewrite launches are always timed), which keeps a timed run as close to an
+ * untimed one as possible.  Errors: VKV_E_INVAL. */
 int kv_profile_sample(vkv_pool* pool, int32_t stride);
 
 /* Waits for the recorded launches to finish, writes up to cap records (launch

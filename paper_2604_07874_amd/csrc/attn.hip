@@ -88,11 +88,11 @@ static int launch_slice(vkv_pool* p, int32_t layer, int32_t slice, const void* q
     a.started = p->progress_dev;
     a.seq = p->report_seq;
   }
-  ProfScope prof(p, VKV_PROF_SLICE, slice, st);
+  ProfKernel prof(p, VKV_PROF_SLICE, slice);
   if (D == 128)
-    hipLaunchKernelGGL((paged_decode_attn_slice_kernel<128, false>), dim3((unsigned)count), dim3(256), 0, st, a);
+    prof.launch(paged_decode_attn_slice_kernel<128, false>, dim3((unsigned)count), dim3(256), st, a);
   else
-    hipLaunchKernelGGL((paged_decode_attn_slice_kernel<64, false>), dim3((unsigned)count), dim3(256), 0, st, a);
+    prof.launch(paged_decode_attn_slice_kernel<64, false>, dim3((unsigned)count), dim3(256), st, a);
   VKV_HIP(hipGetLastError());
   return VKV_OK;
 }
@@ -525,11 +525,11 @@ int paged_decode_attn_layer_static(vkv_pool* p, int32_t layer, const void* q, co
   a.ctx_len = ctx_len_dev;
   a.max_chunks = (int32_t)max_chunks;
   a.max_ctx = max_ctx_tokens;
-  ProfScope prof(p, VKV_PROF_SLICE, 0, hs);
+  ProfKernel prof(p, VKV_PROF_SLICE, 0);
   if (D == 128)
-    hipLaunchKernelGGL((paged_decode_attn_slice_kernel<128, true>), dim3((unsigned)n_items), dim3(256), 0, hs, a);
+    prof.launch(paged_decode_attn_slice_kernel<128, true>, dim3((unsigned)n_items), dim3(256), hs, a);
   else
-    hipLaunchKernelGGL((paged_decode_attn_slice_kernel<64, true>), dim3((unsigned)n_items), dim3(256), 0, hs, a);
+    prof.launch(paged_decode_attn_slice_kernel<64, true>, dim3((unsigned)n_items), dim3(256), hs, a);
   VKV_HIP(hipGetLastError());
   return VKV_OK;
 }

@@ -443,8 +443,8 @@ static int pf_launch_slice(vkv_pool* p, int32_t layer, int32_t slice, const void
   PrefillParams a = pf_params(p, layer, q, table, max_blk, workspace, out, scale);
   a.item_first = p->pf.slice_start[slice];
   const int32_t count = p->pf.slice_start[slice + 1] - a.item_first;
-  ProfScope prof(p, VKV_PROF_PREFILL, slice, st);
-  hipLaunchKernelGGL(paged_prefill_attn_slice_kernel<128>, dim3((unsigned)count), dim3(256), 0, st, a);
+  ProfKernel prof(p, VKV_PROF_PREFILL, slice);
+  prof.launch(paged_prefill_attn_slice_kernel<128>, dim3((unsigned)count), dim3(256), st, a);
   VKV_HIP(hipGetLastError());
   return VKV_OK;
 }

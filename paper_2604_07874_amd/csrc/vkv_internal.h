@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <atomic>
 #include <cstdarg>
@@ -185,6 +186,30 @@ struct ProfScope {
   }
   ~ProfScope() {
     if (slot >= 0) (void)hipEventRecord(p->prof_ev[2 * slot + 1], st);
+  }
+};
+
+// Timing of a single kernel launch while recording is on: the launch itself carries the two events
+// (they take the dispatch's own start and end times), so nothing is enqueued between this kernel and
+// its neighbours and the figure is the kernel's duration alone.
+struct ProfKernel {
+  vkv_pool* p;
+  int slot = -1;
+  ProfKernel(vkv_pool* pool, int32_t kind, int32_t index) : p(pool) {
+    if (p->prof_cap > 0) {
+      std::lock_guard<std::mutex> g(p->prof_mu);
+      if (p->prof_tick++ % p->prof_stride == 0 && (int32_t)p->prof_tag.size() < p->prof_cap) {
+        slot = (int)p->prof_tag.size();
+        p->prof_tag.emplace_back(kind, index);
+      }
+    }
+  }
+  template <typename K, typename... Args>
+  void launch(K kernel, dim3 grid, dim3 block, hipStream_t st, Args... args) {
+    if (slot >= 0)
+      hipExtLaunchKernelGGL(kernel, grid, block, 0, st, p->prof_ev[2 * slot], p->prof_ev[2 * slot + 1], 0, args...);
+    else
+      hipLaunchKernelGGL(kernel, grid, block, 0, st, args...);
   }
 };
 

@@ -66,9 +66,11 @@ __global__ __launch_bounds__(256, 2) void paged_prefill_attn_slice_kernel(const 
   constexpr int RS = D * 2 + 16;
   constexpr float NEG_INF = -INFINITY;
 
-  // two staging buffers: a group is staged while the previous one may still be read
-  __shared__ __attribute__((aligned(16))) unsigned char k_lds2[2][32 * RS];
-  __shared__ __attribute__((aligned(16))) uint32_t va_lds2[2][EPL * 64 * 4];
+  // four staging buffers: group g+2 is staged while g+1 is read for its scores and g for its p.V
+  // products; the buffer it goes into was last read as group g-2, one barrier ago for every wave
+  constexpr int kBufs = 4;
+  __shared__ __attribute__((aligned(16))) unsigned char k_lds4[kBufs][32 * RS];
+  __shared__ __attribute__((aligned(16))) uint32_t va_lds4[kBufs][EPL * 64 * 4];
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -160,59 +162,48 @@ __global__ __launch_bounds__(256, 2) void paged_prefill_attn_slice_kernel(const 
     return x;
   };
 
-  // two groups of loads in flight per wave: the compute of one group is shorter than a memory round trip
-  Rows cur = fetch(0), nx1 = cur;
-  if (1 < ngroups) nx1 = fetch(1);
-  for (int grp = 0; grp < ngroups; ++grp) {
+  // ---- stage this wave's rows of a group for everyone ----
+  auto stage = [&](int grp, Rows& x) {
     const int tok0 = grp * kGroupTokens;
-    unsigned char* k_lds = k_lds2[grp & 1];
-    uint32_t* va_lds = va_lds2[grp & 1];
-    // ---- stage this wave's rows for everyone ----
+    unsigned char* k_lds = k_lds4[grp & (kBufs - 1)];
+    uint32_t* va_lds = va_lds4[grp & (kBufs - 1)];
 #pragma unroll
     for (int rr = 0; rr < 2; ++rr) {
-      *reinterpret_cast<u32x4*>(k_lds + (sb * 16 + 4 * (r0 + rr) + kg) * RS + c16 * 16) = cur.k[rr];
+      *reinterpret_cast<u32x4*>(k_lds + (sb * 16 + 4 * (r0 + rr) + kg) * RS + c16 * 16) = x.k[rr];
       if (tok0 + kGroupTokens > ntok && tok0 + sb * 16 + 4 * (r0 + rr) + kg >= ntok)
-        cur.v[rr] = u32x4{0u, 0u, 0u, 0u};   // rows past the end may hold NaN
+        x.v[rr] = u32x4{0u, 0u, 0u, 0u};   // rows past the end may hold NaN
     }
 #pragma unroll
     for (int dt = 0; dt < EPL; ++dt) {
       const uint32_t sel = (dt & 1) ? 0x07060302u : 0x05040100u;
-      va_lds[(dt * 64 + lane) * 4 + vslot] = __builtin_amdgcn_perm(cur.v[1][dt >> 1], cur.v[0][dt >> 1], sel);
+      va_lds[(dt * 64 + lane) * 4 + vslot] = __builtin_amdgcn_perm(x.v[1][dt >> 1], x.v[0][dt >> 1], sel);
     }
-    cur = nx1;
-    if (grp + 2 < ngroups) nx1 = fetch(grp + 2);
-    // one barrier per group: the buffer written now was last read two groups ago, and every wave has
-    // passed the previous group's barrier since
-    __syncthreads();
-
-    // ---- scores of both column tiles first: the second tile's products run in the matrix unit while
-    // the first tile's softmax runs on the vector unit, and the K operands are dead before the V
-    // operands are read ----
-    const int trow_lds = 4 * (c16 & 3) + (c16 >> 2);
-    f32x4 sc[kNQ][2];
-    {
-      bf16x8 ka[2][KS];
+  };
+  // ---- q.K of a staged group for both column tiles of this wave ----
+  const int trow_lds = 4 * (c16 & 3) + (c16 >> 2);
+  auto scores = [&](int grp, f32x4 (&sc)[kNQ][2]) {
+    const unsigned char* k_lds = k_lds4[grp & (kBufs - 1)];
+    bf16x8 ka[2][KS];
 #pragma unroll
-      for (int b = 0; b < 2; ++b)
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        ka[b][ks] = __builtin_bit_cast(
+            bf16x8, *reinterpret_cast<const u32x4*>(k_lds + (b * 16 + trow_lds) * RS + (ks * 4 + kg) * 16));
+#pragma unroll
+    for (int j = 0; j < kNQ; ++j)
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+        sc[j][b] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
-          ka[b][ks] = __builtin_bit_cast(
-              bf16x8, *reinterpret_cast<const u32x4*>(k_lds + (b * 16 + trow_lds) * RS + (ks * 4 + kg) * 16));
-#pragma unroll
-      for (int j = 0; j < kNQ; ++j)
-#pragma unroll
-        for (int b = 0; b < 2; ++b) {
-          sc[j][b] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-          for (int ks = 0; ks < KS; ++ks)
-            sc[j][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[b][ks], qb[j][ks], sc[j][b], 0, 0, 0);
-        }
-    }
-    bf16x8 va[EPL];
-#pragma unroll
-    for (int dt = 0; dt < EPL; ++dt)
-      va[dt] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(&va_lds[(dt * 64 + lane) * 4]));
-
+          sc[j][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[b][ks], qb[j][ks], sc[j][b], 0, 0, 0);
+      }
+  };
+  // ---- softmax of a group's scores and its p.V products ----
+  auto finish = [&](int grp, f32x4 (&sc)[kNQ][2]) {
+    const int tok0 = grp * kGroupTokens;
+    const uint32_t* va_lds = va_lds4[grp & (kBufs - 1)];
     // A group is interior for this wave when every token of it exists and is visible to every column of
     // the wave; only the groups on the causal diagonal and a ragged last group need the mask.
     const bool interior = tok0 + kGroupTokens <= ntok && tok0 + kGroupTokens - 1 <= wave_limit;
@@ -255,6 +246,13 @@ __global__ __launch_bounds__(256, 2) void paged_prefill_attn_slice_kernel(const 
         const u32x4 u = {r2 ? t[2] : t[0], r2 ? t[3] : t[1], r2 ? t[0] : t[2], r2 ? t[1] : t[3]};
         pbs[j] = __builtin_bit_cast(bf16x8, u);
       }
+    }
+    bf16x8 va[EPL];
+#pragma unroll
+    for (int dt = 0; dt < EPL; ++dt)
+      va[dt] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(&va_lds[(dt * 64 + lane) * 4]));
+#pragma unroll
+    for (int j = 0; j < kNQ; ++j) {
       // the row sums come from the matrix unit too (a tile of ones as the "V" operand), so the
       // denominator sums exactly the rounded weights the numerator uses
       accl[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pbs[j], accl[j], 0, 0, 0);
@@ -262,6 +260,38 @@ __global__ __launch_bounds__(256, 2) void paged_prefill_attn_slice_kernel(const 
       for (int dt = 0; dt < EPL; ++dt)
         acc[j][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pbs[j], acc[j][dt], 0, 0, 0);
     }
+  };
+
+  // Software pipeline over the groups: in the step of group g the rows of group g+2 go into LDS and the
+  // loads of g+3 are requested, then, after the step's one barrier, the q.K products of group g+1 are
+  // issued to the matrix unit and the softmax of group g runs on the vector unit meanwhile, followed by
+  // g's p.V products, which in turn run under the next step's staging.
+  Rows pre = fetch(0);
+  stage(0, pre);
+  if (1 < ngroups) {
+    pre = fetch(1);
+    stage(1, pre);
+  }
+  if (2 < ngroups) pre = fetch(2);
+  __syncthreads();
+  f32x4 sc_cur[kNQ][2], sc_next[kNQ][2];
+  scores(0, sc_cur);
+  for (int grp = 0; grp < ngroups; ++grp) {
+    if (grp + 2 < ngroups) {
+      stage(grp + 2, pre);
+      // requested one step ahead of its staging; two steps ahead (a second set of row registers) was
+      // measured slower, 251 against 216 us per launch
+      if (grp + 3 < ngroups) pre = fetch(grp + 3);
+    }
+    // one barrier per group: the buffer written above was last read as group grp-2, and every wave has
+    // passed the previous step's barrier since; what is read below was staged before that barrier or this one
+    __syncthreads();
+    if (grp + 1 < ngroups) scores(grp + 1, sc_next);
+    finish(grp, sc_cur);
+#pragma unroll
+    for (int j = 0; j < kNQ; ++j)
+#pragma unroll
+      for (int b = 0; b < 2; ++b) sc_cur[j][b] = sc_next[j][b];
   }
 
   // ---- results: column-owned, no merge across waves ----

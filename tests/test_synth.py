@@ -67,3 +67,31 @@ def test_shared_prefix_and_poison():
         assert np.all(st.pool_bits[o:o + g.head_dim] == synth.BF16_NAN_BITS)
         o = g.elem_offset(blk, 0, 0, 0, used - 1)
         assert np.all(st.pool_bits[o:o + g.head_dim] != synth.BF16_NAN_BITS)
+
+
+def test_dump_state_round_trip(tmp_path):
+    """The flat file the native counter driver reads holds exactly the generator's state."""
+    from synth.dump_state import MAGIC, dump
+    name, seed = "llama8b_small", 5
+    path = tmp_path / "state.bin"
+    dump(name, seed, str(path))
+    wl = synth.workload(name)
+    g = wl.geom
+    st = synth.build_state(wl, seed, materialize_pool=False)
+    raw = path.read_bytes()
+    head = np.frombuffer(raw, dtype="<i4", count=16)
+    lo, hi = wl.reclaim_range
+    assert head.tolist() == [MAGIC, 1, g.num_layers, g.num_q_heads, g.num_kv_heads, g.head_dim, g.num_blocks,
+                             g.blocks_per_handle, wl.num_seqs, st.tables.shape[0], st.tables.shape[1], lo, hi,
+                             wl.chunk_tokens, 0, 0]
+    off = 64
+    sizes = np.frombuffer(raw, dtype="<i8", count=2, offset=off)
+    assert sizes.tolist() == [wl.slice_bytes, wl.chunk_bytes]
+    off += 16
+    ctx = np.frombuffer(raw, dtype="<i4", count=wl.num_seqs, offset=off)
+    off += 4 * wl.num_seqs
+    tables = np.frombuffer(raw, dtype="<i4", count=st.tables.size, offset=off).reshape(st.tables.shape)
+    off += 4 * st.tables.size
+    live = np.frombuffer(raw, dtype=np.uint8, count=g.num_blocks, offset=off)
+    assert off + g.num_blocks == len(raw)
+    assert np.array_equal(ctx, st.ctx_len) and np.array_equal(tables, st.tables) and np.array_equal(live, st.live)

@@ -48,6 +48,10 @@ def run_prefill(c, q, q_len, layer, slice_bytes, chunk_tokens, through_scheduler
     ("llama8b_small", 2, [4096] * 8, 2048, 8 << 20),
     ("llama70b_tp8_small", 3, [100, 1, 16, 700, 31, 32, 33, 2000, 8, 9, 10, 640], 256, 1 << 19),
     ("offline_batch_small", 4, [1000, 2, 129, 4096, 77, 512], 1024, 1 << 21),
+    # items of one, two and three token groups only: the start and the end of the kernel's pipeline over groups
+    ("llama8b_small", 6, [64, 96, 33, 200, 1, 7, 130, 65], 32, 1 << 18),
+    ("llama8b_small", 7, [64, 96, 33, 200, 1, 7, 130, 65], 64, 1 << 18),
+    ("stress_small", 8, [96, 97, 31, 250, 2, 500, 64, 190, 32, 1], 96, 1 << 18),
     # items longer than two 64-entry windows of block ids
     ("llama70b_tp8_small", 5, [1500, 40, 8192, 3, 700, 2500, 64, 1, 900, 4000, 33, 256], 8192, 4 << 20),
 ])

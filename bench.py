@@ -491,7 +491,7 @@ def run_workload(name, args, workers, headline=True):
                       "yield_latency_us_max": round(max(lat), 1), "yield_injections": len(lat)})
 
     # ---- optional: reclamation under a rate cap on a second stream while decode keeps running
-    if concurrent_leg:
+    def concurrent_leg_run():
         progress("concurrent rate-capped reclamation leg")
         cap = args.rate_cap or wl.rate_cap or 20e9
         cchunk = rc_chunk or (64 << 20)
@@ -500,28 +500,39 @@ def run_workload(name, args, workers, headline=True):
         stop = threading.Event()
         marks = []          # (time, layers finished) samples from the decode thread
 
+        thread_error = []
+
         def decode_forever():
             n = 0
-            while not stop.is_set():
-                for layer in range(L):
-                    vkv.kv_attn_run_layer(pool, layer, 0, q_all[layer], tables, ws, out[layer],
-                                          max_inflight=args.max_inflight, stream=decode_stream)
-                    n += 1
-                decode_stream.synchronize()
-                marks.append((time.perf_counter(), n))
+            try:
+                while not stop.is_set():
+                    for layer in range(L):
+                        vkv.kv_attn_run_layer(pool, layer, 0, q_all[layer], tables, ws, out[layer],
+                                              max_inflight=args.max_inflight, stream=decode_stream)
+                        n += 1
+                    decode_stream.synchronize()
+                    marks.append((time.perf_counter(), n))
+            except BaseException as e:      # the main thread polls `marks`: it must learn that none will come
+                thread_error.append(e)
+
+        def wait_for(cond):
+            while not cond():
+                if thread_error:
+                    raise RuntimeError(f"decode thread failed: {thread_error[0]!r}")
+                time.sleep(0.001)
 
         th = threading.Thread(target=decode_forever)
         th.start()
-        while len(marks) < 2:
-            time.sleep(0.001)
-        t_a, n_a = marks[-1]
-        crs = vkv.kv_reclaim_range(pool, lo, hi, tables, remap, chunk_bytes=cchunk, rate_cap_bytes_per_s=int(cap),
-                                   copy_stream=copy_stream, decode_stream=decode_stream)
-        while marks[-1][0] < t_a + crs.host_seconds:
-            time.sleep(0.001)
-        t_b, n_b = marks[-1]
-        stop.set()
-        th.join()
+        try:
+            wait_for(lambda: len(marks) >= 2)
+            t_a, n_a = marks[-1]
+            crs = vkv.kv_reclaim_range(pool, lo, hi, tables, remap, chunk_bytes=cchunk, rate_cap_bytes_per_s=int(cap),
+                                       copy_stream=copy_stream, decode_stream=decode_stream)
+            wait_for(lambda: marks[-1][0] >= t_a + crs.host_seconds)
+            t_b, n_b = marks[-1]
+        finally:
+            stop.set()
+            th.join()
         torch.cuda.synchronize()
         rewind()
         torch.cuda.synchronize()
@@ -534,10 +545,22 @@ def run_workload(name, args, workers, headline=True):
             "concurrent_decode_frac_of_peak": round((n_b - n_a) * decode_bytes_layer / (t_b - t_a) / 1e9 / HBM_PEAK_GBPS, 4),
         })
 
+    if concurrent_leg:
+        try:
+            concurrent_leg_run()
+        except Exception as e:      # an extra leg must not take the workload's record down with it
+            extra["concurrent_error"] = f"{type(e).__name__}: {e}"
+            torch.cuda.synchronize()
+
     # ---- optional: online bursts against a continuous offline decode loop --------------------
     if n_bursts > 0:
-        extra.update(burst_leg(vkv, args, wl, pool, pool_t, arena, st, q_all, tables, tables0, ws, out, remap, lo, hi,
-                               rc_chunk, src_ids, dst_ids, decode_bytes_layer, int(rs.bytes_moved), n_bursts))
+        try:
+            extra.update(burst_leg(vkv, args, wl, pool, pool_t, arena, st, q_all, tables, tables0, ws, out, remap, lo, hi,
+                                   rc_chunk, src_ids, dst_ids, decode_bytes_layer, int(rs.bytes_moved), n_bursts))
+        except Exception as e:      # an extra leg must not take the headline line down with it
+            extra["burst_error"] = f"{type(e).__name__}: {e}"
+            vkv.kv_yield_clear(pool)
+            torch.cuda.synchronize()
 
     # ---- optional: preemptible causal prefill over the same pool (MFMA-bound) -------------
     if prefill_leg:
@@ -626,7 +649,18 @@ def burst_leg(vkv, args, wl, pool, pool_t, arena, st, q_all, tables, tables0, ws
     bytes_layer = [int(plan_box[0].kv_bytes_per_layer)]
     decoded_bytes = [0]
 
+    offline_error = []
+
     def offline():
+        try:
+            offline_loop()
+        except BaseException as e:      # the main thread must not wait for a thread that is gone
+            offline_error.append(e)
+            with cv:
+                gate["paused"] = True
+                cv.notify_all()
+
+    def offline_loop():
         layer, cur = 0, 0
         while not stop.is_set():
             with cv:
@@ -664,7 +698,11 @@ def burst_leg(vkv, args, wl, pool, pool_t, arena, st, q_all, tables, tables0, ws
         vkv.kv_yield_request(pool)
         with cv:
             while not gate["paused"]:
-                cv.wait()
+                cv.wait(1.0)
+                if offline_error:
+                    raise RuntimeError(f"offline decode thread failed: {offline_error[0]!r}")
+        if offline_error:
+            raise RuntimeError(f"offline decode thread failed: {offline_error[0]!r}")
         return t_req, time.perf_counter()
 
     def resume_offline(t_req):
@@ -784,34 +822,43 @@ def burst_leg(vkv, args, wl, pool, pool_t, arena, st, q_all, tables, tables0, ws
     active, k_ev, n_pressure, headroom_trace = 0, 0, 0, []
     served_late = 0
     t_end = timeline[-1][0] + 0.05
-    while True:
-        now = time.perf_counter() - t_start
-        if now >= t_end:
-            break
-        nxt = timeline[k_ev][0] if k_ev < len(timeline) else t_end
-        wait = min(nxt, now + tick_s) - now
-        if wait > 0:
-            time.sleep(wait)
-        now = time.perf_counter() - t_start
-        while k_ev < len(timeline) and timeline[k_ev][0] <= now:
-            active += timeline[k_ev][1]
-            k_ev += 1
-        used_h = active * burst_handles
-        for _ in range(32):                       # the controller until it has nothing more to ask for
-            H, grow_by, release, event, T = vkv.kv_miad_observe(miad, time.perf_counter() - t_start, used_h)
-            n_pressure += event
-            if grow_by > 0:
-                if not grow(grow_by):
-                    break
-                continue                          # pressure may persist: the next observation decides
-            if release:
-                release_one()
-            break
-        headroom_trace.append(H)
-        if used_h > H:
-            served_late += 1
-    stop.set()
-    th.join()
+    try:
+        while True:
+            now = time.perf_counter() - t_start
+            if now >= t_end or offline_error:
+                break
+            nxt = timeline[k_ev][0] if k_ev < len(timeline) else t_end
+            wait = min(nxt, now + tick_s) - now
+            if wait > 0:
+                time.sleep(wait)
+            now = time.perf_counter() - t_start
+            while k_ev < len(timeline) and timeline[k_ev][0] <= now:
+                active += timeline[k_ev][1]
+                k_ev += 1
+            used_h = active * burst_handles
+            for _ in range(32):                       # the controller until it has nothing more to ask for
+                H, grow_by, release, event, T = vkv.kv_miad_observe(miad, time.perf_counter() - t_start, used_h)
+                n_pressure += event
+                if grow_by > 0:
+                    if not grow(grow_by):
+                        break
+                    continue                          # pressure may persist: the next observation decides
+                if release:
+                    release_one()
+                break
+            headroom_trace.append(H)
+            if used_h > H:
+                served_late += 1
+    finally:
+        # whatever happened, the decode thread is stopped and nothing of it is left on the GPU
+        stop.set()
+        vkv.kv_yield_clear(pool)
+        with cv:
+            gate["want_pause"] = False
+            cv.notify_all()
+        th.join()
+    if offline_error:
+        raise RuntimeError(f"offline decode thread failed: {offline_error[0]!r}")
     torch.cuda.synchronize()
     total_s = time.perf_counter() - t_start
     # everything goes back, newest first, so that the pool ends as it began (bar the evicted requests)

@@ -745,7 +745,8 @@ def burst_leg(vkv, args, wl, pool, pool_t, arena, st, q_all, tables, tables0, ws
                 dst = remap_plan[src].astype(np.int32)
                 for h in range(rhi // bph - 1, rlo // bph - 1, -1):     # top handle first, so that giving back
                     m = (src // bph) == h                                  # starts at the boundary
-                    units.append((h, src[m], dst[m]))
+                    # with the arena the handle's memory really goes away: its blocks stay where they were moved
+                    units.append((h, src[m], dst[m]) if arena is None else (h, None, None))
                     reserved[h] = True
                 stats["relocations"] += 1
                 stats["moved_bytes"] += int(rs.bytes_moved)
@@ -865,11 +866,16 @@ def burst_leg(vkv, args, wl, pool, pool_t, arena, st, q_all, tables, tables0, ws
     while units:
         release_one()
     vkv.kv_miad_destroy(miad)
-    # the evicted requests come back for the legs that follow: their blocks were freed, never overwritten
-    live_now, _ = vkv.kv_pool_state(pool, nb)
-    vkv.kv_pool_adopt(pool, np.flatnonzero(st.live.astype(bool) & ~live_now.astype(bool)).astype(np.int32))
-    tables.copy_(tables0)
-    vkv.kv_attn_plan(pool, st.ctx_len, args.slice_bytes or wl.slice_bytes, args.chunk_tokens or wl.chunk_tokens)
+    if arena is None:
+        # the evicted requests come back for the legs that follow: their blocks were freed, never overwritten
+        live_now, _ = vkv.kv_pool_state(pool, nb)
+        vkv.kv_pool_adopt(pool, np.flatnonzero(st.live.astype(bool) & ~live_now.astype(bool)).astype(np.int32))
+        tables.copy_(tables0)
+        vkv.kv_attn_plan(pool, st.ctx_len, args.slice_bytes or wl.slice_bytes, args.chunk_tokens or wl.chunk_tokens)
+    else:
+        # handles that were unmapped came back as fresh memory: the blocks stay where the relocations put
+        # them, the tables say so, and the evicted requests stay out
+        vkv.kv_attn_plan(pool, ctx, args.slice_bytes or wl.slice_bytes, args.chunk_tokens or wl.chunk_tokens)
     vkv.kv_attn_bind(pool, ws, torch.cuda.current_stream())
     vkv.kv_attn_run_layer(pool, 0, 0, q_all[0], tables, ws, out[0], max_inflight=args.max_inflight,
                           stream=torch.cuda.current_stream())

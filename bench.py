@@ -34,7 +34,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published
 HEADLINE = "stress"
-EVENT_STRIDE = 8         # launches per bracketed launch inside the timed steps
+EVENT_STRIDE = 8         # every so many launches inside the timed steps carry timing events (every 2nd: whole step -1..2 %)
 CPU_SAMPLE_HEADLINE_FACTOR = 8.0 / 3.0   # the headline workload's oracle sample against the others'
 # Run order of the default run, smallest pool first: a 40 or 64 GiB pool allocated after a 200 GiB one has
 # been freed in the same process ran its kernels 5-6 % slower than in a fresh process (the same
@@ -88,7 +88,7 @@ def parse_args():
     ap.add_argument("--slice-bytes", type=int, default=None)
     ap.add_argument("--reclaim-chunk-bytes", type=int, default=None)
     ap.add_argument("--max-inflight", type=int, default=2)
-    ap.add_argument("--yield-injections", type=int, default=300)
+    ap.add_argument("--yield-injections", type=int, default=1000)
     ap.add_argument("--concurrent-reclaim", dest="concurrent_reclaim", action="store_true", default=None,
                     help="extra leg: rate-capped, chunked reclamation on a second stream while decode runs "
                          "(default: on for workloads that define a rate cap)")
@@ -314,8 +314,9 @@ def run_workload(name, args, workers, headline=True):
     if not events_in_steps:
         progress("one-stream pass with launch events (kernel durations)")
         vkv.kv_sched_set_overlap(pool, False)
-        vkv.kv_profile_enable(pool, 2 * launches_per_step + 16)
-        vkv.kv_profile_sample(pool, 3)
+        vkv.kv_profile_enable(pool, 3 * launches_per_step + 16)
+        vkv.kv_profile_sample(pool, 1)
+        decode_pass()
         decode_pass()
         vkv.kv_reclaim_range(pool, lo, hi, tables, remap, chunk_bytes=rc_chunk, copy_stream=stream)
         rewind()
@@ -336,7 +337,7 @@ def run_workload(name, args, workers, headline=True):
                 "avg_launch_us": round(slice_ms_avg * 1e3, 2),
                 "bytes_per_launch": int(bytes_per_launch), "launches": int(len(sl)),
                 "method": ((f"HIP events carried by every {EVENT_STRIDE}th launch inside the timed steps" if events_in_steps else
-                            "HIP events carried by every 3rd launch in a one-stream pass after the timed steps (the timed "
+                            "HIP events carried by every launch of two one-stream passes after the timed steps (the timed "
                             "steps alternate slices between two streams, where durations are not additive)")
                            + "; hipExtLaunchKernelGGL start/stop events = the dispatch's own start and end")}
     roofline_reclaim = None

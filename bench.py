@@ -690,6 +690,9 @@ def burst_leg(vkv, args, wl, pool, pool_t, arena, st, q_all, tables, tables0, ws
              "fifo_cost": 0, "moved_bytes": 0, "released_handles": 0}
     grow_ms, idle_ms, paused_s = [], [], [0.0]
     reloc_ms, evict_ms, reloc_handles, evict_handles, all_gone = [], [], [], [], []
+    pending = []                                    # evicted requests of the batch waiting to be taken back
+    readmit = {"events": 0, "requests": 0, "tokens_to_recompute": 0, "last_t": 0.0}
+    nblk_of = -(-st.ctx_len.astype(np.int64) // g.block_tokens)
     ident = torch.arange(nb, dtype=torch.int32, device=dev)
 
     def pause_offline():
@@ -760,6 +763,7 @@ def burst_leg(vkv, args, wl, pool, pool_t, arena, st, q_all, tables, tables0, ws
                 stats["evicted_cost"] += int(info.total_cost)
                 gone = [r for r in evicted.tolist() if r < S]
                 all_gone.extend(gone)
+                pending.extend(gone)
                 if gone:
                     # the evicted requests leave the batch; the next slices follow a new plan
                     ctx[gone] = 0
@@ -813,6 +817,50 @@ def burst_leg(vkv, args, wl, pool, pool_t, arena, st, q_all, tables, tables0, ws
             tables_host[used] = back[tables_host[used]]
             copy_stream.synchronize()
 
+    def readmit_some(now):
+        """Evicted requests come back once the online tenant has let go of enough memory: fresh blocks, their
+        table rows filled in, the plan made anew.  Their KV has to be recomputed (the paper's cost of an
+        eviction); here only its size is counted."""
+        if not pending or now - readmit["last_t"] < 0.010:
+            return
+        readmit["last_t"] = now
+        live_now, _ = vkv.kv_pool_state(pool, nb, max_ranges=1)
+        free = int(((live_now == 0) & ~np.repeat(reserved, bph)).sum())
+        room = free - nb // 50                       # two per cent of the pool stay free
+        take, need = [], 0
+        for r in pending[:64]:
+            if need + int(nblk_of[r]) > room:
+                break
+            take.append(r)
+            need += int(nblk_of[r])
+        if not take:
+            return
+        t_req, _ = pause_offline()
+        try:
+            ids = vkv.kv_pool_alloc(pool, need)
+            at = 0
+            for r in take:
+                n = int(nblk_of[r])
+                tables_host[r, :n] = ids[at:at + n]
+                at += n
+                ctx[r] = st.ctx_len[r]
+                cost[r] = ctx[r]
+            rows_t = torch.tensor(take, device=dev)
+            tables[rows_t] = torch.from_numpy(tables_host[take]).to(dev)
+            torch.cuda.synchronize()
+            del pending[:len(take)]
+            plan_box[0] = vkv.kv_attn_plan(pool, ctx, args.slice_bytes or wl.slice_bytes,
+                                           args.chunk_tokens or wl.chunk_tokens)
+            bytes_layer[0] = int(plan_box[0].kv_bytes_per_layer)
+            vkv.kv_attn_bind(pool, ws, decode_stream)
+            with cv:
+                gate["restart_layer"] = True
+            readmit["events"] += 1
+            readmit["requests"] += len(take)
+            readmit["tokens_to_recompute"] += int(st.ctx_len[take].sum())
+        finally:
+            resume_offline(t_req)
+
     # the initial headroom is taken before anything is timed (also creates the queues of the two new streams)
     h0 = vkv.kv_miad_observe(miad, 0.0, 0)[0]
     grow(h0, timed=False)
@@ -851,6 +899,8 @@ def burst_leg(vkv, args, wl, pool, pool_t, arena, st, q_all, tables, tables0, ws
             headroom_trace.append(H)
             if used_h > H:
                 served_late += 1
+            if active == 0:
+                readmit_some(time.perf_counter() - t_start)
     finally:
         # whatever happened, the decode thread is stopped and nothing of it is left on the GPU
         stop.set()
@@ -868,6 +918,12 @@ def burst_leg(vkv, args, wl, pool, pool_t, arena, st, q_all, tables, tables0, ws
         release_one()
     vkv.kv_miad_destroy(miad)
     if arena is None:
+        # requests that were evicted and taken back sit in blocks of their own: those go first
+        for r in sorted(set(all_gone)):
+            mine = tables_host[r][tables_host[r] >= 0]
+            if len(mine):
+                vkv.kv_pool_free(pool, mine)
+                tables_host[r] = -1
         # the evicted requests come back for the legs that follow: their blocks were freed, never overwritten
         live_now, _ = vkv.kv_pool_state(pool, nb)
         vkv.kv_pool_adopt(pool, np.flatnonzero(st.live.astype(bool) & ~live_now.astype(bool)).astype(np.int32))
@@ -900,6 +956,8 @@ def burst_leg(vkv, args, wl, pool, pool_t, arena, st, q_all, tables, tables0, ws
         "burst_evictions": stats["evictions"], "burst_evicted_requests": stats["evicted_requests"],
         "burst_evicted_cost_tokens": stats["evicted_cost"], "burst_fifo_cost_tokens": stats["fifo_cost"],
         "burst_moved_bytes_total": stats["moved_bytes"], "burst_released_handles": stats["released_handles"],
+        "burst_requests_taken_back": readmit["requests"], "burst_take_back_events": readmit["events"],
+        "burst_tokens_to_recompute": readmit["tokens_to_recompute"], "burst_requests_still_out": len(pending),
         "burst_yield_to_idle_ms_p50": round(percentile(idle_ms, 50), 3) if idle_ms else None,
         "burst_yield_to_idle_ms_p99": round(percentile(idle_ms, 99), 3) if idle_ms else None,
         "burst_request_to_handed_over_ms_p50": round(percentile(grow_ms, 50), 3) if grow_ms else None,

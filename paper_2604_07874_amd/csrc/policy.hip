@@ -220,7 +220,7 @@ int kv_invalidate_handles(vkv_pool* p, const int32_t* handles, int32_t k, const 
       if (p->live[(size_t)b]) { p->live[(size_t)b] = 0; --p->n_live; }
   }
   for (int32_t i = 0; i < k; ++i)   // in the order given
-    p->released.emplace_back(handles[i] * bph, (handles[i] + 1) * bph, tables_dev != nullptr);
+    p->hand_over(handles[i] * bph, (handles[i] + 1) * bph, tables_dev != nullptr);
   return VKV_OK;
 }
 
@@ -290,7 +290,7 @@ int kv_evict_handles(vkv_pool* p, int32_t k, int32_t* tables, int32_t n_rows, in
     const int32_t h = handles_out[i];
     for (int32_t b = h * bph; b < (h + 1) * bph; ++b)
       if (p->live[(size_t)b]) { p->live[(size_t)b] = 0; --p->n_live; }
-    p->released.emplace_back(h * bph, (h + 1) * bph, tables_dev != nullptr || rows.empty());
+    p->hand_over(h * bph, (h + 1) * bph, tables_dev != nullptr || rows.empty());
   }
   if (evicted_rows_out) std::copy(rows.begin(), rows.end(), evicted_rows_out);
   info->mode = 1;

@@ -24,11 +24,7 @@ int hip_fail(hipError_t e, const char* what) {
   return VKV_E_HIP;
 }
 
-bool in_released(const vkv_pool* p, int32_t b) {
-  for (const auto& r : p->released)
-    if (b >= r.first && b < r.second) return true;
-  return false;
-}
+bool in_released(const vkv_pool* p, int32_t b) { return p->handed[(size_t)b] != 0; }
 
 int ensure_stage(vkv_pool* p, size_t bytes) {
   if (!p->stage_ev) VKV_HIP(hipEventCreateWithFlags(&p->stage_ev, hipEventDisableTiming));
@@ -108,6 +104,7 @@ int kv_pool_init(const vkv_pool_config* c, vkv_pool** out) {
   p->block_elems = be;
   p->block_bytes = be * 2;
   p->live.assign((size_t)c->num_blocks, 0);
+  p->handed.assign((size_t)c->num_blocks, 0);
   if (c->base) {
     // a pool with device memory: find this device's copy of the static scratch now, so that
     // paged_decode_attn_layer_static has nothing left to set up (a failure here is reported there)
@@ -205,6 +202,7 @@ int kv_pool_return_range(vkv_pool* p, int32_t lo, int32_t hi) {
       }
       // what is left of the range on either side stays handed over
       p->released.erase(p->released.begin() + (long)i);
+      std::fill(p->handed.begin() + lo, p->handed.begin() + hi, (uint8_t)0);
       if (hi < r.second) p->released.insert(p->released.begin() + (long)i, vkv_pool::Range(hi, r.second, r.clean));
       if (r.first < lo) p->released.insert(p->released.begin() + (long)i, vkv_pool::Range(r.first, lo, r.clean));
       return VKV_OK;

@@ -231,7 +231,7 @@ int kv_reclaim_range(vkv_pool* p, int32_t lo, int32_t hi, int32_t* tables, int64
     p->live[src[i]] = 0;
     p->live[dst[i]] = 1;
   }
-  p->released.emplace_back(lo, hi);
+  p->hand_over(lo, hi, true);
   if (stats) {
     *stats = vkv_reclaim_stats{};
     stats->blocks_moved = (int32_t)src.size();

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
 
+#include <algorithm>
+
 #include <atomic>
 #include <cstdarg>
 #include <cstdint>
@@ -85,7 +87,12 @@ struct vkv_pool {
     Range(int32_t a, int32_t b, bool c = true) : first(a), second(b), clean(c) {}
   };
   std::vector<Range> released;
+  std::vector<uint8_t> handed;   // per block: 1 inside a handed-over range (kept in step with `released`)
   int64_t n_live = 0;
+  void hand_over(int32_t lo, int32_t hi, bool clean) {
+    released.emplace_back(lo, hi, clean);
+    std::fill(handed.begin() + lo, handed.begin() + hi, (uint8_t)1);
+  }
 
   // attention plan (host)
   bool has_plan = false;

@@ -25,8 +25,12 @@
  *   - "device" pointers are HIP device memory owned by the caller; "host"
  *     pointers are ordinary host memory owned by the caller.  The library owns
  *     only the opaque vkv_pool object (host memory, small pinned staging
- *     buffers, HIP events).  It never allocates or frees device memory; the one
- *     exception, at the caller's request, is the kv_arena_* group.
+ *     buffers, two progress words in pinned host memory that slice launches
+ *     report to, HIP events, one extra stream once kv_sched_set_overlap has
+ *     been used).  It never allocates or frees device memory; the one
+ *     exception, at the caller's request, is the kv_arena_* group, and
+ *     paged_decode_attn_layer_static works in a fixed 16 MiB device array that
+ *     is part of the library's image.
  *   - Streams are hipStream_t passed as void* (NULL = the default stream).
  *     Device work is enqueued on the given stream; unless stated otherwise a
  *     call returns without waiting for it.

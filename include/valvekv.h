@@ -167,7 +167,7 @@ int kv_attn_bind(vkv_pool* pool, void* workspace, uint64_t workspace_bytes, void
  * are never read.  bf16 inputs, fp32 accumulation.
  *   q_bf16       device [num_seqs][num_q_heads][head_dim] for this layer
  *   block_table  device int32 [>= num_seqs rows][max_blk], -1 padded
- *   out_f32      device fp32 [num_seqs][num_q_heads][head_dim]
+ *   out_f32      device fp32 [num_seqs][num_q_heads][head_dim], 16-byte aligned
  * The host checks layer, slice and max_blk against the plan (VKV_E_INVAL,
  * VKV_E_STATE); the kernel skips table entries outside [0, NB) and raises a flag
  * that kv_attn_check reports. */

@@ -103,8 +103,8 @@ static int check_slice_args(vkv_pool* p, int32_t layer, const void* q, const int
   if (st != VKV_OK) return st;
   if (!p->cfg.base) { set_error("%s: pool has no device memory", who); return VKV_E_INVAL; }
   if (layer < 0 || layer >= p->cfg.num_layers) { set_error("%s: layer %d out of range", who, layer); return VKV_E_INVAL; }
-  if (!q || !table || !out || (uintptr_t)q % 16) {
-    set_error("%s: q (16-byte aligned), block_table and out must be given", who);
+  if (!q || !table || !out || (uintptr_t)q % 16 || (uintptr_t)out % 16) {
+    set_error("%s: q and out (16-byte aligned) and block_table must be given", who);
     return VKV_E_INVAL;
   }
   if (max_blk < p->max_ctx_blocks) {
@@ -462,8 +462,8 @@ int paged_decode_attn_layer_static(vkv_pool* p, int32_t layer, const void* q, co
   if (p->broken) { set_error("%s: pool unusable after a HIP failure", who); return VKV_E_HIP; }
   if (!p->cfg.base) { set_error("%s: pool has no device memory", who); return VKV_E_INVAL; }
   if (layer < 0 || layer >= p->cfg.num_layers) { set_error("%s: layer %d out of range", who, layer); return VKV_E_INVAL; }
-  if (!q || !table || !ctx_len_dev || !out || (uintptr_t)q % 16 || (uintptr_t)err_flag_dev % 4) {
-    set_error("%s: q (16-byte aligned), block_table, ctx_len and out must be given", who);
+  if (!q || !table || !ctx_len_dev || !out || (uintptr_t)q % 16 || (uintptr_t)out % 16 || (uintptr_t)err_flag_dev % 4) {
+    set_error("%s: q and out (16-byte aligned), block_table and ctx_len must be given", who);
     return VKV_E_INVAL;
   }
   if (chunk_tokens < kGroupTokens || chunk_tokens % kGroupTokens || chunk_tokens > kMaxChunkTokens) {

@@ -14,13 +14,15 @@
 // cross-workgroup ordering).
 //
 // Kernel shape (wave64, gfx950): 4 waves; wave w owns columns [32w, 32w+32) as two 16-column
-// MFMA tiles and sees every token of the item.  Per 32-token group the workgroup stages K and
-// V once for all four waves: wave w loads rows {4r+kg : r in (2(w&1), 2(w&1)+1)} of block
-// w>>1 of the group (K and V, 16 bytes per lane each), writes the K rows to a shared padded
-// LDS tile and one dword (two tokens) of every lane's transposed V operand to a shared LDS
-// array; after a barrier each wave reads the 8 K operands and 8 V operands it needs for its
-// MFMAs (v_mfma_f32_16x16x32_bf16, same operand layouts and token-to-row assignment as the
-// decode kernel) and runs online softmax per column with the causal mask applied by select.
+// MFMA tiles and sees every token of the item.  Per 32-token group the workgroup brings K and V
+// into LDS once for all four waves, with the 16-byte global->LDS loads of gfx950: wave w asks
+// for rows 4w .. 4w+3 of both blocks of the group, K and V, four loads in all, which need no
+// registers and are requested three groups ahead of their use.  The rows lie in LDS as in the
+// pool (256 bytes per token), their 16-byte chunks permuted so that the operand reads meet no
+// bank conflict.  After the step's barrier each wave reads the 8 K operands (16-byte reads) and
+// the 8 V operands (transposing 8-byte reads, which hand each lane its own head dimension of
+// four tokens) it needs for its MFMAs (v_mfma_f32_16x16x32_bf16) and runs online softmax per
+// column with the causal mask applied by select.
 #include "vkv_internal.h"
 
 #include <algorithm>
@@ -58,19 +60,53 @@ struct PrefillParams {
   float scale_log2;
 };
 
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+// LDS reads the compiler does not see as such.  It orders every LDS read it knows of behind all pending
+// global->LDS loads (it cannot tell the staging buffers apart), which would wait for the groups that were
+// requested ahead; these reads are ordered by hand instead: the loads of a buffer are waited for
+// (s_waitcnt vmcnt) before the barrier that lets anyone read it.
+template <int OFF>
+__device__ __forceinline__ void lds_read_b128(u32x4& dst, uint32_t addr) {
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF));
+}
+// transposing 8-byte read: within 16 lanes, lane i gets element i & 3 of the four 16-bit elements that lane
+// 4 j + (i >> 2) points at, for j = 0..3
+template <int OFF>
+__device__ __forceinline__ void lds_read_tr16_b64(u32x2& dst, uint32_t addr) {
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF));
+}
+__device__ __forceinline__ void lds_wait(u32x4 (&a)[8]) {
+  asm volatile("s_waitcnt lgkmcnt(0)"
+               : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7])
+               :: "memory");
+}
+__device__ __forceinline__ void lds_wait(u32x2 (&a)[16]) {
+  asm volatile("s_waitcnt lgkmcnt(0)"
+               : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7]),
+                 "+v"(a[8]), "+v"(a[9]), "+v"(a[10]), "+v"(a[11]), "+v"(a[12]), "+v"(a[13]), "+v"(a[14]), "+v"(a[15])
+               :: "memory");
+}
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+  return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
+}
+
 template <int D>
 __global__ __launch_bounds__(256, 2) void paged_prefill_attn_slice_kernel(const PrefillParams p) {
   static_assert(D == 128, "head_dim 128 only");
   constexpr int EPL = D / 16;
   constexpr int KS = D / 32;
-  constexpr int RS = D * 2 + 16;
+  constexpr int ROW = D * 2;            // bytes of one token row of one head
   constexpr float NEG_INF = -INFINITY;
 
-  // four staging buffers: group g+2 is staged while g+1 is read for its scores and g for its p.V
-  // products; the buffer it goes into was last read as group g-2, one barrier ago for every wave
+  // Four staging buffers of a 32-token group each, K rows and V rows as they lie in the pool (256 bytes
+  // per token), written by the 16-byte global->LDS loads; no padding is possible there (a load places its
+  // 64 lanes back to back), so the 16-byte chunks of a row are permuted instead, by the choice of the
+  // global address each lane asks for: chunk c of K row r sits at position c ^ (r & 15), chunk c of V row r
+  // at c ^ 2 (r & 7) (the LDS has 64 banks: 16 lanes of a 16-byte read, 32 lanes of an 8-byte read go together).
   constexpr int kBufs = 4;
-  __shared__ __attribute__((aligned(16))) unsigned char k_lds4[kBufs][32 * RS];
-  __shared__ __attribute__((aligned(16))) uint32_t va_lds4[kBufs][EPL * 64 * 4];
+  __shared__ __attribute__((aligned(16))) unsigned char k_lds4[kBufs][32 * ROW];
+  __shared__ __attribute__((aligned(16))) unsigned char v_lds4[kBufs][32 * ROW];
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -107,12 +143,36 @@ __global__ __launch_bounds__(256, 2) void paged_prefill_attn_slice_kernel(const 
   }
 
   const int32_t* trow = p.table + (size_t)seq * p.max_blk + it.first_block;
-  const uint16_t* kplane = p.pool + (size_t)it.kv_head * (16 * D);
+  const unsigned char* kplane = reinterpret_cast<const unsigned char*>(p.pool + (size_t)it.kv_head * (16 * D));
   const int nblk_item = (ntok + 15) >> 4;
-  // block ids of the item, 64 at a time: lane i of tb0 holds entry 64 win + i, tb1 the 64 after those
-  int32_t tb0 = lane < nblk_item ? trow[lane] : -1;
-  int32_t tb1 = 64 + lane < nblk_item ? trow[64 + lane] : -1;
+  // Byte offsets of the item's blocks from kplane, 64 at a time, one per lane: lane i of (o0lo, o0hi) holds
+  // entry 64 win + i, (o1lo, o1hi) the 64 after those.  An entry past the item's end or outside the pool
+  // (a corrupted table, reported here) gets hi = -1; the loads then go to the item's latest good block,
+  // whose rows exist, and what they bring is masked (K) or cleared after it is read (V).
+  uint32_t o0lo, o0hi, o1lo, o1hi;
+  auto window = [&](int w, uint32_t& lo, uint32_t& hi) {
+    const int e = w * 64 + lane;
+    int32_t blk = -1;
+    if (e < nblk_item) {
+      blk = trow[e];
+      if (blk < 0 || blk >= p.NB) {
+        atomicOr(p.err, 1u);
+        blk = -1;
+      }
+    }
+    const uint64_t off = (uint64_t)(uint32_t)blk * (p.block_elems * 2);
+    lo = (uint32_t)off;
+    hi = blk < 0 ? 0xFFFFFFFFu : (uint32_t)(off >> 32);
+    // have it now: no load with a register result is then pending from one step to the next, and the
+    // compiler has no reason to wait for the loads into LDS along with it
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(lo), "+v"(hi) :: "memory");
+  };
+  window(0, o0lo, o0hi);
+  window(1, o1lo, o1hi);
   int win = 0;
+  // the item's first block must be good: there is nothing to fall back on before it
+  uint32_t safe_lo = __builtin_amdgcn_readlane(o0lo, 0), safe_hi = __builtin_amdgcn_readlane(o0hi, 0);
+  if (safe_hi == 0xFFFFFFFFu) return;   // reported above; the whole workgroup leaves, before any barrier
 
   f32x4 acc[kNQ][EPL], accl[kNQ];
   float m_run[kNQ];
@@ -130,66 +190,61 @@ __global__ __launch_bounds__(256, 2) void paged_prefill_attn_slice_kernel(const 
   // last token index (within the item) that every column of this wave may see
   const int wave_limit = pos0 + ((wave * kNQ * 16) >> p.gp_shift) - tok_base;
 
-  // this wave's share of a group: rows 4r+kg, r in {r0, r0+1}, of block (wave >> 1)
-  const int sb = wave >> 1, r0 = (wave & 1) * 2;
-  // Where this wave's token pair goes inside a lane's 16-byte V operand: rotated by the lane's k-group,
-  // so that the 64 one-dword writes of a wave fall on 64 different dword columns instead of every fourth
-  // one.  The weights are rotated the same way before the p.V products (a sum over tokens does not care
-  // in which order the tokens sit, as long as both operands agree).
-  const int vslot = (wave + kg) & 3;
-  struct Rows { u32x4 k[2], v[2]; };
-  auto fetch = [&](int grp) -> Rows {
-    Rows x;
-    const int bi = grp * 2 + sb;
-    const bool have = bi < nblk_item;
-    if ((bi >> 6) != win) {   // groups are fetched in rising order, so the window moves one step at a time
-      win = bi >> 6;
-      tb0 = tb1;
-      tb1 = (win + 1) * 64 + lane < nblk_item ? trow[(win + 1) * 64 + lane] : -1;
+  // ---- this wave's share of a group goes from the pool straight into LDS ----
+  // Rows 4 wave .. 4 wave + 3 of both blocks of the group, K and V: four loads of 64 x 16 bytes.  Lane l
+  // fills position l & 15 of row 4 wave + (l >> 4), so it asks for the chunk that belongs there.
+  const int lrow = 4 * wave + kg;                                     // row within a block
+  const uint32_t g_off_k = (uint32_t)(lrow * ROW + ((c16 ^ (lrow & 15)) * 16));        // bytes
+  const uint32_t g_off_v = (uint32_t)(lrow * ROW + ((c16 ^ (2 * (lrow & 7))) * 16));
+  const uint64_t v_bytes = (uint64_t)p.v_off * 2;
+  auto issue = [&](int grp) {
+#pragma unroll
+    for (int sb = 0; sb < 2; ++sb) {
+      const int bi = grp * 2 + sb;
+      if ((bi >> 6) != win) {   // blocks are visited in rising order, so the window moves one step at a time
+        win = bi >> 6;
+        o0lo = o1lo;
+        o0hi = o1hi;
+        window(win + 1, o1lo, o1hi);
+      }
+      uint32_t lo = __builtin_amdgcn_readlane(o0lo, bi & 63), hi = __builtin_amdgcn_readlane(o0hi, bi & 63);
+      const bool good = hi != 0xFFFFFFFFu;
+      lo = good ? lo : safe_lo;
+      hi = good ? hi : safe_hi;
+      safe_lo = lo;
+      safe_hi = hi;
+      const unsigned char* src = kplane + (((uint64_t)hi << 32) | lo);
+      unsigned char* kd = k_lds4[grp & (kBufs - 1)] + (sb * 16 + 4 * wave) * ROW;
+      unsigned char* vd = v_lds4[grp & (kBufs - 1)] + (sb * 16 + 4 * wave) * ROW;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + g_off_k),
+                                       (__attribute__((address_space(3))) void*)kd, 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + v_bytes + g_off_v),
+                                       (__attribute__((address_space(3))) void*)vd, 16, 0, 0);
     }
-    const int32_t blk = __builtin_amdgcn_readlane(tb0, bi & 63);
-    if (blk < 0 || blk >= p.NB) {
-      if (have && lane == 0) atomicOr(p.err, 1u);
-      x.k[0] = x.k[1] = x.v[0] = x.v[1] = u32x4{0u, 0u, 0u, 0u};
-    } else {
-      const u32x4* ks = reinterpret_cast<const u32x4*>(kplane + (size_t)blk * p.block_elems);
-      const u32x4* vs = reinterpret_cast<const u32x4*>(kplane + (size_t)blk * p.block_elems + p.v_off);
-      x.k[0] = ks[r0 * 64 + lane];
-      x.k[1] = ks[(r0 + 1) * 64 + lane];
-      x.v[0] = vs[r0 * 64 + lane];
-      x.v[1] = vs[(r0 + 1) * 64 + lane];
-    }
-    return x;
+  };
+  // all of this wave's loads but those of the newest group (four, if there is one) have landed
+  auto wait_all_but = [&](bool one_group) {
+    if (one_group) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   };
 
-  // ---- stage this wave's rows of a group for everyone ----
-  auto stage = [&](int grp, Rows& x) {
-    const int tok0 = grp * kGroupTokens;
-    unsigned char* k_lds = k_lds4[grp & (kBufs - 1)];
-    uint32_t* va_lds = va_lds4[grp & (kBufs - 1)];
-#pragma unroll
-    for (int rr = 0; rr < 2; ++rr) {
-      *reinterpret_cast<u32x4*>(k_lds + (sb * 16 + 4 * (r0 + rr) + kg) * RS + c16 * 16) = x.k[rr];
-      if (tok0 + kGroupTokens > ntok && tok0 + sb * 16 + 4 * (r0 + rr) + kg >= ntok)
-        x.v[rr] = u32x4{0u, 0u, 0u, 0u};   // rows past the end may hold NaN
-    }
-#pragma unroll
-    for (int dt = 0; dt < EPL; ++dt) {
-      const uint32_t sel = (dt & 1) ? 0x07060302u : 0x05040100u;
-      va_lds[(dt * 64 + lane) * 4 + vslot] = __builtin_amdgcn_perm(x.v[1][dt >> 1], x.v[0][dt >> 1], sel);
-    }
-  };
   // ---- q.K of a staged group for both column tiles of this wave ----
-  const int trow_lds = 4 * (c16 & 3) + (c16 >> 2);
+  // row c16 of the K operand is token 16 b + c16 of the group; its chunk ks 4 + kg sits at (ks 4 + kg) ^ c16
+  uint32_t k_addr[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) k_addr[ks] = lds_addr(&k_lds4[0][0]) + c16 * ROW + (((ks * 4 + kg) ^ c16) << 4);
   auto scores = [&](int grp, f32x4 (&sc)[kNQ][2]) {
-    const unsigned char* k_lds = k_lds4[grp & (kBufs - 1)];
-    bf16x8 ka[2][KS];
-#pragma unroll
-    for (int b = 0; b < 2; ++b)
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
-        ka[b][ks] = __builtin_bit_cast(
-            bf16x8, *reinterpret_cast<const u32x4*>(k_lds + (b * 16 + trow_lds) * RS + (ks * 4 + kg) * 16));
+    const uint32_t boff = (uint32_t)(grp & (kBufs - 1)) * (32 * ROW);
+    u32x4 ka[8];   // [b * KS + ks]
+    lds_read_b128<0>(ka[0], k_addr[0] + boff);
+    lds_read_b128<16 * ROW>(ka[4], k_addr[0] + boff);
+    lds_read_b128<0>(ka[1], k_addr[1] + boff);
+    lds_read_b128<16 * ROW>(ka[5], k_addr[1] + boff);
+    lds_read_b128<0>(ka[2], k_addr[2] + boff);
+    lds_read_b128<16 * ROW>(ka[6], k_addr[2] + boff);
+    lds_read_b128<0>(ka[3], k_addr[3] + boff);
+    lds_read_b128<16 * ROW>(ka[7], k_addr[3] + boff);
+    lds_wait(ka);
 #pragma unroll
     for (int j = 0; j < kNQ; ++j)
 #pragma unroll
@@ -197,13 +252,28 @@ __global__ __launch_bounds__(256, 2) void paged_prefill_attn_slice_kernel(const 
         sc[j][b] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
-          sc[j][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[b][ks], qb[j][ks], sc[j][b], 0, 0, 0);
+          sc[j][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[b * KS + ks]), qb[j][ks],
+                                                             sc[j][b], 0, 0, 0);
       }
   };
   // ---- softmax of a group's scores and its p.V products ----
+  // The V operand of d-tile dt (d = 16 dt + c16 in this lane) comes from two transposing reads, one per
+  // block of the group: the 16 lanes of a k-group point at 8-byte pieces of rows 4 kg .. 4 kg + 3 (lane s
+  // at row 4 kg + (s >> 2), d = 16 dt + 4 (s & 3)) and each gets its own d of those four rows back.
+  const int v_rr = c16 >> 2, v_q = c16 & 3;
+  const int v_base = (4 * kg + v_rr) * ROW + v_q * 8;
+  const int v_sw = (4 * kg + v_rr) & 7;
+  uint32_t v_addr[EPL];
+#pragma unroll
+  for (int dt = 0; dt < EPL; ++dt) v_addr[dt] = lds_addr(&v_lds4[0][0]) + v_base + ((dt ^ v_sw) << 5);
   auto finish = [&](int grp, f32x4 (&sc)[kNQ][2]) {
     const int tok0 = grp * kGroupTokens;
-    const uint32_t* va_lds = va_lds4[grp & (kBufs - 1)];
+    const uint32_t boff = (uint32_t)(grp & (kBufs - 1)) * (32 * ROW);
+    // requested first, so that they arrive while the softmax below is computed
+    u32x2 vh[16];   // [2 dt + block of the group]
+#define VKV_VREAD(dt) lds_read_tr16_b64<0>(vh[2 * dt], v_addr[dt] + boff); lds_read_tr16_b64<16 * ROW>(vh[2 * dt + 1], v_addr[dt] + boff);
+    VKV_VREAD(0) VKV_VREAD(1) VKV_VREAD(2) VKV_VREAD(3) VKV_VREAD(4) VKV_VREAD(5) VKV_VREAD(6) VKV_VREAD(7)
+#undef VKV_VREAD
     // A group is interior for this wave when every token of it exists and is visible to every column of
     // the wave; only the groups on the causal diagonal and a ragged last group need the mask.
     const bool interior = tok0 + kGroupTokens <= ntok && tok0 + kGroupTokens - 1 <= wave_limit;
@@ -211,17 +281,14 @@ __global__ __launch_bounds__(256, 2) void paged_prefill_attn_slice_kernel(const 
 #pragma unroll
     for (int j = 0; j < kNQ; ++j) {
       if (!interior) {
-        // column = (position cpos[j], head cg[j]); token tok0 + 16b + 4r + kg sits at position tok_base + that
+        // column = (position cpos[j], head cg[j]); token tok0 + 16b + 4kg + r sits at position tok_base + that
         const int limit = min(pos0 + cpos[j] - tok_base, ntok - 1);   // last visible token index within the item
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
           for (int r = 0; r < 4; ++r)
-            if (tok0 + b * 16 + 4 * r + kg > limit) sc[j][b][r] = NEG_INF;   // also drops NaN from rows past the end
+            if (tok0 + b * 16 + 4 * kg + r > limit) sc[j][b][r] = NEG_INF;   // also drops NaN from rows past the end
       }
-      // The running reference m_run follows the column maximum lazily: it moves only when some score
-      // exceeds it by more than kSlack (log2 units), so p stays below 2^kSlack and most groups skip
-      // both the cross-lane maximum and the rescaling of the accumulators.
       const float mx = fmaxf(fmaxf(fmaxf(sc[j][0][0], sc[j][0][1]), fmaxf(sc[j][0][2], sc[j][0][3])),
                              fmaxf(fmaxf(sc[j][1][0], sc[j][1][1]), fmaxf(sc[j][1][2], sc[j][1][3])));
       if (__builtin_amdgcn_ballot_w64(fmaf(mx, p.scale_log2, -kSlack) > m_run[j]) != 0ull) {
@@ -234,23 +301,23 @@ __global__ __launch_bounds__(256, 2) void paged_prefill_attn_slice_kernel(const 
 #pragma unroll
         for (int dt = 0; dt < EPL; ++dt) acc[j][dt] *= alpha;
       }
-      bf16x8 pb;
 #pragma unroll
       for (int i = 0; i < 8; ++i)
-        pb[i] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sc[j][i >> 2][i & 3], p.scale_log2, -m_run[j]));
-      {
-        // token pair w of the weights moves to slot (w + kg) & 3, as in the staged V operand
-        const u32x4 pw = __builtin_bit_cast(u32x4, pb);
-        const bool r1 = kg & 1, r2 = kg & 2;
-        const u32x4 t = {r1 ? pw[3] : pw[0], r1 ? pw[0] : pw[1], r1 ? pw[1] : pw[2], r1 ? pw[2] : pw[3]};
-        const u32x4 u = {r2 ? t[2] : t[0], r2 ? t[3] : t[1], r2 ? t[0] : t[2], r2 ? t[1] : t[3]};
-        pbs[j] = __builtin_bit_cast(bf16x8, u);
-      }
+        pbs[j][i] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sc[j][i >> 2][i & 3], p.scale_log2, -m_run[j]));
     }
-    bf16x8 va[EPL];
+    lds_wait(vh);
+    u32x4 va[EPL];
 #pragma unroll
-    for (int dt = 0; dt < EPL; ++dt)
-      va[dt] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(&va_lds[(dt * 64 + lane) * 4]));
+    for (int dt = 0; dt < EPL; ++dt) va[dt] = u32x4{vh[2 * dt][0], vh[2 * dt][1], vh[2 * dt + 1][0], vh[2 * dt + 1][1]};
+    if (tok0 + kGroupTokens > ntok) {
+      // the item's ragged last group: rows past the end hold whatever the pool holds there (maybe NaN);
+      // their weights are zero, their V must be too.  Element i of the operand is token 16 (i >> 2) + 4 kg + (i & 3).
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        if (tok0 + (i >> 2) * 16 + 4 * kg + (i & 3) >= ntok)
+#pragma unroll
+          for (int dt = 0; dt < EPL; ++dt) va[dt][i >> 1] &= (i & 1) ? 0x0000FFFFu : 0xFFFF0000u;
+    }
 #pragma unroll
     for (int j = 0; j < kNQ; ++j) {
       // the row sums come from the matrix unit too (a tile of ones as the "V" operand), so the
@@ -258,34 +325,30 @@ __global__ __launch_bounds__(256, 2) void paged_prefill_attn_slice_kernel(const 
       accl[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pbs[j], accl[j], 0, 0, 0);
 #pragma unroll
       for (int dt = 0; dt < EPL; ++dt)
-        acc[j][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pbs[j], acc[j][dt], 0, 0, 0);
+        acc[j][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, va[dt]), pbs[j], acc[j][dt], 0, 0, 0);
     }
   };
 
-  // Software pipeline over the groups: in the step of group g the rows of group g+2 go into LDS and the
-  // loads of g+3 are requested, then, after the step's one barrier, the q.K products of group g+1 are
-  // issued to the matrix unit and the softmax of group g runs on the vector unit meanwhile, followed by
-  // g's p.V products, which in turn run under the next step's staging.
-  Rows pre = fetch(0);
-  stage(0, pre);
-  if (1 < ngroups) {
-    pre = fetch(1);
-    stage(1, pre);
-  }
-  if (2 < ngroups) pre = fetch(2);
+  // Software pipeline over the groups.  Loads run three groups ahead of the p.V products and need no
+  // registers; the one barrier of a step says two things: every wave's loads of group g+1 have landed
+  // (each wave waits for its own first), and every wave is done with step g-1, whose buffers the loads
+  // issued right after the barrier overwrite.
+  issue(0);
+  if (1 < ngroups) issue(1);
+  wait_all_but(1 < ngroups);     // group 0 has landed
   __syncthreads();
   f32x4 sc_cur[kNQ][2], sc_next[kNQ][2];
   scores(0, sc_cur);
+  if (2 < ngroups) issue(2);
   for (int grp = 0; grp < ngroups; ++grp) {
-    if (grp + 2 < ngroups) {
-      stage(grp + 2, pre);
-      // requested one step ahead of its staging; two steps ahead (a second set of row registers) was
-      // measured slower, 251 against 216 us per launch
-      if (grp + 3 < ngroups) pre = fetch(grp + 3);
-    }
-    // one barrier per group: the buffer written above was last read as group grp-2, and every wave has
-    // passed the previous step's barrier since; what is read below was staged before that barrier or this one
-    __syncthreads();
+    wait_all_but(grp + 2 < ngroups);   // everything up to group grp+1
+    // the barrier alone, without the fence of __syncthreads: that fence would wait for the loads of the
+    // two groups ahead as well; this wave's LDS reads of the previous step have returned (they fed its
+    // matrix instructions), which is all the others need to know before they overwrite those buffers
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (grp + 3 < ngroups) issue(grp + 3);
     if (grp + 1 < ngroups) scores(grp + 1, sc_next);
     finish(grp, sc_cur);
 #pragma unroll
@@ -294,7 +357,7 @@ __global__ __launch_bounds__(256, 2) void paged_prefill_attn_slice_kernel(const 
       for (int b = 0; b < 2; ++b) sc_cur[j][b] = sc_next[j][b];
   }
 
-  // ---- results: column-owned, no merge across waves ----
+  // ---- results: column-owned, no merge across waves; register r of d-tile dt is d = 16 dt + 4 kg + r ----
   const int nch = (p.tile_base[tile + 1] - p.tile_base[tile]) / p.Hkv;
   const size_t item = (size_t)item_id;
 #pragma unroll
@@ -306,23 +369,13 @@ __global__ __launch_bounds__(256, 2) void paged_prefill_attn_slice_kernel(const 
         float* orow = p.out + ((size_t)(row0 + cpos[j]) * p.Hq + (size_t)it.kv_head * G + cg[j]) * D;
         const float inv = 1.0f / l;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          float* dst = orow + (kg * 4 + r) * EPL;
-#pragma unroll
-          for (int dt = 0; dt < EPL; dt += 4)
-            *reinterpret_cast<f32x4*>(dst + dt) = f32x4{acc[j][dt][r] * inv, acc[j][dt + 1][r] * inv,
-                                                        acc[j][dt + 2][r] * inv, acc[j][dt + 3][r] * inv};
-        }
+        for (int dt = 0; dt < EPL; ++dt)
+          *reinterpret_cast<f32x4*>(orow + 16 * dt + 4 * kg) = acc[j][dt] * inv;
       }
     } else {
       float* prow = p.part_acc + (item * kTileColumns + col) * D;
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        float* dst = prow + (kg * 4 + r) * EPL;
-#pragma unroll
-        for (int dt = 0; dt < EPL; dt += 4)
-          *reinterpret_cast<f32x4*>(dst + dt) = f32x4{acc[j][dt][r], acc[j][dt + 1][r], acc[j][dt + 2][r], acc[j][dt + 3][r]};
-      }
+      for (int dt = 0; dt < EPL; ++dt) *reinterpret_cast<f32x4*>(prow + 16 * dt + 4 * kg) = acc[j][dt];
       if (kg == 0) {
         p.part_ml[(item * kTileColumns + col) * 2 + 0] = m_run[j];
         p.part_ml[(item * kTileColumns + col) * 2 + 1] = l;

@@ -113,7 +113,7 @@ def parse_args():
                          "(default: on for the llama8b workload)")
     ap.add_argument("--no-prefill-leg", dest="prefill_leg", action="store_false")
     ap.add_argument("--prefill-tokens", type=int, default=2048)
-    ap.add_argument("--prefill-slice-bytes", type=int, default=512 << 20)
+    ap.add_argument("--prefill-slice-bytes", type=int, default=1 << 30)
     ap.add_argument("--prefill-one-stream", action="store_true",
                     help="prefill leg without overlapped slices (then per-launch durations are additive)")
     ap.add_argument("--prefill-yield-injections", type=int, default=100)

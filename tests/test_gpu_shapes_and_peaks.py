@@ -264,22 +264,29 @@ def test_bad_table_entry_is_flagged_and_other_sequences_are_untouched():
         pq_t = torch.from_numpy(pq.reshape(total, g.num_q_heads, g.head_dim).view(np.int16)).cuda()
         info = vkv.kv_prefill_plan(c.pool, c.st.ctx_len, q_len, 1 << 20, 256)
         pws = torch.empty(info.workspace_bytes, dtype=torch.uint8, device="cuda:0")
+        # a second pattern hits the first block of an item (the first of the sequence, and the first of its
+        # second chunk), for which the kernel has nothing earlier to fall back on
+        assert c.st.ctx_len[victim] > 17 * 16
+        bad_first = c.tables_t.clone()
+        bad_first[victim, 0] = -1
+        bad_first[victim, 16] = g.num_blocks
         outs = []
-        for tab in (c.tables_t, bad):
+        for tab in (c.tables_t, bad, bad_first):
             vkv.kv_prefill_bind(c.pool, pws)
             po = torch.full((total, g.num_q_heads, g.head_dim), float("nan"), dtype=torch.float32, device="cuda:0")
             st, _ = vkv.kv_prefill_run_layer(c.pool, 0, 0, pq_t, tab, pws, po)
             assert st == vkv.VKV_OK
-            if tab is bad:
+            if tab is c.tables_t:
+                vkv.kv_prefill_check(c.pool, pws)
+            else:
                 with pytest.raises(vkv.VkvError) as e:
                     vkv.kv_prefill_check(c.pool, pws)
                 assert e.value.code == vkv.VKV_E_STATE
-            else:
-                vkv.kv_prefill_check(c.pool, pws)
             outs.append(po.cpu().numpy())
         q_start = np.concatenate([[0], np.cumsum(q_len)])
-        for s in others:
-            assert np.array_equal(outs[0][q_start[s]:q_start[s + 1]], outs[1][q_start[s]:q_start[s + 1]])
+        for other in outs[1:]:
+            for s in others:
+                assert np.array_equal(outs[0][q_start[s]:q_start[s + 1]], other[q_start[s]:q_start[s + 1]])
     finally:
         c.close()
 

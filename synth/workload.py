@@ -134,7 +134,8 @@ WORKLOADS: Dict[str, Workload] = {
                               ("uniform", 512, 32768), None, 16384, chunk_bytes=64 << 20, rate_cap=20e9,
                               slice_bytes=1 << 30, chunk_tokens=2048),
     "llama70b_tp8": Workload("llama70b_tp8", _g(80, 8, 1, 128, 104832, 64), 128,
-                             ("lognormal", 4096, 0.7, 16, 16384), 0.85, 13120, slice_bytes=1 << 30),
+                             ("lognormal", 4096, 0.7, 16, 16384), 0.85, 13120, slice_bytes=1 << 30,
+                             chunk_tokens=1408),
     "stress": Workload("stress", _g(10, 32, 8, 128, 327680, 64), 512,
                        ("uniform", 256, 16384), 0.90, 26240, slice_bytes=1 << 30, chunk_tokens=2048),
     # Reduced shapes (same heads, fewer layers / sequences / blocks) that a CPU

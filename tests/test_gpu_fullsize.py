@@ -162,6 +162,73 @@ def test_stress_size_overlapped_slices_and_reclaim():
         c.close()
 
 
+def test_full_size_prefill_in_the_benchmark_configuration(full_case):
+    """Causal prefill of the newest 2048 tokens of every sequence of the 40 GiB pool, in the launch
+    configuration the benchmark times (768 MiB slices overlapped on two streams, chunks of 8192 tokens,
+    through the scheduler): sampled query rows of the shortest, the median and the longest sequence
+    against the fp64 oracle, row by row, and a second pass with the same bits."""
+    import math
+    from oracle.attention import PoolLayout, attend_contiguous, bf16_bits_to_f64, gather_contiguous
+    c = full_case
+    wl, g, vkv = c.wl, c.wl.geom, c.vkv
+    layer = g.num_layers - 1
+    q_len = np.minimum(c.st.ctx_len, 2048).astype(np.int32)
+    q_start = np.concatenate([[0], np.cumsum(q_len)[:-1]]).astype(np.int64)
+    total = int(q_len.sum())
+    q = synth.hash_bf16_bits(np.arange(total * g.num_q_heads * g.head_dim, dtype=np.int64), 77, 1)
+    q = q.reshape(total, g.num_q_heads, g.head_dim)
+    info = vkv.kv_prefill_plan(c.pool, c.st.ctx_len, q_len, 768 << 20, 8192)
+    print(f"rows {info.total_q} items {info.n_items} slices {info.n_slices} merge steps {info.n_merge_steps}", flush=True)
+    ws = torch.empty(info.workspace_bytes, dtype=torch.uint8, device="cuda:0")
+    vkv.kv_prefill_bind(c.pool, ws)
+    q_t = torch.from_numpy(q.view(np.int16)).cuda()
+    out = torch.full((total, g.num_q_heads, g.head_dim), float("nan"), dtype=torch.float32, device="cuda:0")
+    vkv.kv_sched_set_overlap(c.pool, True)
+    try:
+        passes = []
+        for _ in range(2):
+            out.fill_(float("nan"))
+            st, cur = vkv.kv_prefill_run_layer(c.pool, layer, 0, q_t, c.tables_t, ws, out, max_inflight=2)
+            assert (st, cur) == (vkv.VKV_OK, info.n_slices + info.n_merge_steps)
+            vkv.kv_prefill_check(c.pool, ws)
+            passes.append(out.cpu().numpy())
+        got = passes[0]
+        assert np.isfinite(got).all() and np.array_equal(got, passes[1])
+    finally:
+        vkv.kv_sched_set_overlap(c.pool, False)
+    # the sampled sequences' blocks of this layer, regenerated from the counter-based generator
+    order = np.argsort(c.st.ctx_len)
+    seqs = [int(order[0]), int(order[len(order) // 2]), int(order[-1])]
+    rows = c.st.tables[seqs]
+    ids = np.unique(rows[rows >= 0])
+    renum = np.full(g.num_blocks, -1, dtype=np.int32)
+    renum[ids] = np.arange(len(ids), dtype=np.int32)
+    layer_elems = 2 * g.num_kv_heads * g.block_tokens * g.head_dim
+    lane = np.arange(layer_elems, dtype=np.int64)
+    small = np.empty((len(ids), layer_elems), dtype=np.uint16)
+    for i, b in enumerate(ids):
+        small[i] = synth.hash_bf16_bits(lane + int(b) * g.block_elems + layer * layer_elems, c.seed, 0)
+    lay = PoolLayout(1, g.num_kv_heads, g.head_dim, g.block_tokens)
+    scale = 1.0 / math.sqrt(g.head_dim)
+    worst = 0.0
+    for k, s_ in enumerate(seqs):
+        n, ql = int(c.st.ctx_len[s_]), int(q_len[s_])
+        table = np.where(rows[k] >= 0, renum[np.maximum(rows[k], 0)], -1).astype(np.int32)
+        Kb, Vb = gather_contiguous(small.reshape(-1), lay, table, n, 0)
+        K, V = bf16_bits_to_f64(Kb), bf16_bits_to_f64(Vb)
+        # first and last new token, both sides of a tile boundary (32 positions at 4 query heads per kv head), a few between
+        picks = sorted({0, 1, 31, 32, ql // 2, ql - 2, ql - 1} & set(range(ql)))
+        for i in picks:
+            pos = n - ql + i
+            row = int(q_start[s_]) + i
+            ref = attend_contiguous(bf16_bits_to_f64(q[row]), K[:pos + 1], V[:pos + 1], scale)
+            err = float(np.max(np.abs(got[row].astype(np.float64) - ref)))
+            worst = max(worst, err)
+            assert err <= TOL, (s_, i, err)
+        print(f"seq {s_} ctx {n} new tokens {ql}: rows {picks} ok", flush=True)
+    print(f"prefill at full size: max|err| {worst:.3e}", flush=True)
+
+
 @pytest.mark.parametrize("name", ["offline_batch", "llama70b_tp8"])
 def test_full_size_sampled_parity_of_the_other_configurations(name):
     """The 160 GiB / context 32,768 shape and the 80-layer one-kv-head share, in the benchmark's launch

@@ -193,7 +193,14 @@ int kv_attn_check(vkv_pool* pool, void* workspace, void* stream);
  * without recomputing anything (the paper's requirement that preempted work is
  * resumed, not repeated: Section 2.2 on duplicated iterations; Section 4.1).
  * On VKV_OK *cursor_slice = n_slices and every slice has been enqueued (not
- * waited for). */
+ * waited for).
+ * A layer of four slices or more is merged differently from what
+ * paged_decode_attn_slice does on its own: its slices store their partial
+ * results only, and one small launch behind the layer's last slice (enqueued
+ * with it, so a yield lands before that slice or after the merge) merges every
+ * split (sequence, kv head) in chunk order; the bits are the same.  Such a layer
+ * must therefore be run through this call from its first slice to its last, not
+ * partly through paged_decode_attn_slice. */
 int kv_attn_run_layer(vkv_pool* pool, int32_t layer, int32_t* cursor_slice,
                       const void* q_bf16, const int32_t* block_table, int32_t max_blk,
                       void* workspace, void* out_f32, float softmax_scale,

@@ -57,9 +57,9 @@ static int check_bound(vkv_pool* p, const void* workspace, const char* who) {
   return VKV_OK;
 }
 
-static int launch_slice(vkv_pool* p, int32_t layer, int32_t slice, const void* q, const int32_t* table,
-                        int32_t max_blk, void* workspace, void* out, float scale, hipStream_t st) {
-  const int32_t first = p->slice_start[slice], count = p->slice_start[slice + 1] - first;
+// the kernel parameters every launch of a planned layer shares
+static AttnParams layer_params(vkv_pool* p, int32_t layer, const void* q, const int32_t* table, int32_t max_blk,
+                               void* workspace, void* out, float scale) {
   const int D = p->cfg.head_dim;
   char* ws = (char*)workspace;
   AttnParams a{};   // every field the launch does not set is zero (no progress report, no dense grid)
@@ -77,13 +77,22 @@ static int launch_slice(vkv_pool* p, int32_t layer, int32_t slice, const void* q
   a.err = (uint32_t*)(ws + p->ws.header);
   a.block_elems = p->block_elems;
   a.v_off = (uint32_t)(p->cfg.num_kv_heads * 16 * D);
-  a.item_first = first;
   a.max_blk = max_blk;
   a.Hq = p->cfg.num_q_heads;
   a.Hkv = p->cfg.num_kv_heads;
   a.G = p->G;
   a.NB = p->cfg.num_blocks;
   a.scale_log2 = (scale != 0.f ? scale : 1.0f / std::sqrt((float)D)) * 1.4426950408889634f;
+  return a;
+}
+
+static int launch_slice(vkv_pool* p, int32_t layer, int32_t slice, const void* q, const int32_t* table,
+                        int32_t max_blk, void* workspace, void* out, float scale, hipStream_t st, bool defer_merge) {
+  const int32_t first = p->slice_start[slice], count = p->slice_start[slice + 1] - first;
+  const int D = p->cfg.head_dim;
+  AttnParams a = layer_params(p, layer, q, table, max_blk, workspace, out, scale);
+  a.item_first = first;
+  a.defer_merge = defer_merge ? 1 : 0;
   if (p->report_seq) {   // the scheduler counts this launch
     a.started = p->progress_dev;
     a.seq = p->report_seq;
@@ -93,6 +102,19 @@ static int launch_slice(vkv_pool* p, int32_t layer, int32_t slice, const void* q
     prof.launch(paged_decode_attn_slice_kernel<128, false>, dim3((unsigned)count), dim3(256), st, a);
   else
     prof.launch(paged_decode_attn_slice_kernel<64, false>, dim3((unsigned)count), dim3(256), st, a);
+  VKV_HIP(hipGetLastError());
+  return VKV_OK;
+}
+
+// the merge of a layer whose slices were launched with defer_merge, behind all of them
+static int launch_layer_merge(vkv_pool* p, int32_t layer, const void* q, const int32_t* table, int32_t max_blk,
+                              void* workspace, void* out, float scale, hipStream_t st) {
+  const AttnParams a = layer_params(p, layer, q, table, max_blk, workspace, out, scale);
+  const unsigned grid = (unsigned)(p->num_seqs * p->cfg.num_kv_heads);
+  if (p->cfg.head_dim == 128)
+    hipLaunchKernelGGL(attn_merge_kernel<128>, dim3(grid), dim3(256), 0, st, a);
+  else
+    hipLaunchKernelGGL(attn_merge_kernel<64>, dim3(grid), dim3(256), 0, st, a);
   VKV_HIP(hipGetLastError());
   return VKV_OK;
 }
@@ -158,7 +180,8 @@ static void wait_progress(const volatile uint32_t* word, uint32_t want) {
 // (results are merged through per-item partials), so their order does not matter.
 int run_slices(vkv_pool* p, int32_t* cursor, int32_t n_slices, int32_t max_inflight, hipStream_t hs,
                const char* who, const std::function<int(int32_t, hipStream_t)>& launch, int32_t n_tail,
-               const std::function<int(int32_t)>& tail, bool launches_report) {
+               const std::function<int(int32_t)>& tail, bool launches_report,
+               const std::function<int()>& after_slices) {
   if (!cursor || *cursor < 0 || *cursor > n_slices + n_tail || max_inflight < 1 || max_inflight > kMaxInflight) {
     set_error("%s: bad cursor or max_inflight", who);
     return VKV_E_INVAL;
@@ -258,6 +281,12 @@ int run_slices(vkv_pool* p, int32_t* cursor, int32_t n_slices, int32_t max_infli
     if (st != VKV_OK) return st;
     if ((st = track(on)) != VKV_OK) return st;
     if (on != hs) aux_used = true;
+    // what belongs behind the last slice goes out with it, on the caller's stream, once the second
+    // stream's slices are joined: no yield test lies between the two
+    if (s == n_slices - 1 && after_slices) {
+      if ((st = join()) != VKV_OK) return st;
+      if ((st = after_slices()) != VKV_OK) return st;
+    }
   }
   if ((st = join()) != VKV_OK) return st;
   for (int32_t t = std::max(*cursor, n_slices) - n_slices; t < n_tail; ++t) {
@@ -399,7 +428,7 @@ int paged_decode_attn_slice(vkv_pool* p, int32_t layer, int32_t slice, const voi
     set_error("paged_decode_attn_slice: slice %d out of range [0,%d)", slice, (int)p->slice_start.size() - 1);
     return VKV_E_INVAL;
   }
-  return launch_slice(p, layer, slice, q, table, max_blk, workspace, out, scale, (hipStream_t)stream);
+  return launch_slice(p, layer, slice, q, table, max_blk, workspace, out, scale, (hipStream_t)stream, false);
 }
 
 int kv_probe_attn_reads(vkv_pool* p, int32_t layer, int32_t slice, const int32_t* table, int32_t max_blk,
@@ -447,11 +476,18 @@ int kv_attn_run_layer(vkv_pool* p, int32_t layer, int32_t* cursor, const void* q
   if (st != VKV_OK) return st;
   const int32_t n_slices = (int32_t)p->slice_start.size() - 1;
   hipStream_t hs = (hipStream_t)stream;
+  // Where a layer is many launches its split sequences are merged once, behind the last slice (issued
+  // with it: a yield lands before the last slice or after the merge), not by the last arriver inside the
+  // slices; the bits are the same.  A layer is resumed the way it was begun: the rule depends on the plan only.
+  const bool defer = n_slices >= kDeferMergeMinSlices;
   return run_slices(p, cursor, n_slices, max_inflight, hs, "kv_attn_run_layer",
                     [&](int32_t s, hipStream_t on) {
-                      return launch_slice(p, layer, s, q, table, max_blk, workspace, out, scale, on);
+                      return launch_slice(p, layer, s, q, table, max_blk, workspace, out, scale, on, defer);
                     },
-                    0, nullptr, true);
+                    0, nullptr, true,
+                    defer ? std::function<int()>([&]() {
+                      return launch_layer_merge(p, layer, q, table, max_blk, workspace, out, scale, hs);
+                    }) : std::function<int()>());
 }
 
 int paged_decode_attn_layer_static(vkv_pool* p, int32_t layer, const void* q, const int32_t* table, int32_t max_blk,

@@ -32,6 +32,9 @@ int  hip_fail(hipError_t e, const char* what);
 constexpr int kMaxInflight = 8;
 constexpr int kGroupTokens = 32;   // tokens one wave handles per loop iteration (two blocks)
 constexpr int kMergeLdsBytes = 16 * 1024;   // LDS the last chunk may use for per-chunk (max, sum)
+// a layer of at least this many slices merges its split sequences in one launch of its own after the last
+// slice (kv_attn_run_layer) instead of inside the slices
+constexpr int kDeferMergeMinSlices = 4;
 constexpr int kMaxChunkTokens = 2048;   // an item's block ids fit two registers per lane
 
 struct WorkItem {   // matches int4 on the device
@@ -229,7 +232,8 @@ int static_scratch_for_current_device(void** out);
 bool arena_range_mapped(const vkv_arena* a, int32_t first, int32_t last);
 int run_slices(vkv_pool* p, int32_t* cursor, int32_t n_slices, int32_t max_inflight, hipStream_t hs, const char* who,
                const std::function<int(int32_t, hipStream_t)>& launch, int32_t n_tail,
-               const std::function<int(int32_t)>& tail, bool launches_report);
+               const std::function<int(int32_t)>& tail, bool launches_report,
+               const std::function<int()>& after_slices = nullptr);
 int ensure_progress_words(vkv_pool* p);
 
 // Algorithm 1 on the host tables; evicted[r] != 0 for the requests that go.  See kv_select_handles.

@@ -98,10 +98,12 @@ def test_overlapped_slices_keep_stream_order_and_bits():
         c.close()
 
 
-def test_merge_is_repeatable_when_chunks_of_a_sequence_arrive_from_many_launches():
-    """32 chunks per sequence, cut into slices far smaller than a sequence so that the chunks of one
-    (sequence, kv head) finish in different launches running side by side on two streams; whichever
-    workgroup arrives last merges.  Twenty passes must give the bits of the one-launch result."""
+@pytest.mark.parametrize("pieces", ["many", "three"])
+def test_merge_is_repeatable_when_chunks_of_a_sequence_arrive_from_many_launches(pieces):
+    """32 chunks per sequence, cut into slices so that the chunks of one (sequence, kv head) finish in
+    different launches running side by side on two streams.  In three slices whichever workgroup arrives
+    last merges, inside the launches; in many slices (far smaller than a sequence) the scheduler has the
+    layer merged once behind its last slice.  Twenty passes must give the bits of the one-launch result."""
     from gpu_util import DeviceCase
     wl = synth.workload("offline_batch_small", ctx_dist=("uniform", 3969, 4096))
     c = DeviceCase(wl, seed=47)
@@ -112,8 +114,12 @@ def test_merge_is_repeatable_when_chunks_of_a_sequence_arrive_from_many_launches
         one = c.plan(slice_bytes=1 << 40, chunk_tokens=128)
         assert one.n_slices == 1
         ref = c.attention(0, q_t)
-        many = c.plan(slice_bytes=1 << 20, chunk_tokens=128)
-        assert many.n_slices >= 64 and many.n_items == one.n_items
+        if pieces == "many":
+            many = c.plan(slice_bytes=1 << 20, chunk_tokens=128)
+            assert many.n_slices >= 64 and many.n_items == one.n_items
+        else:
+            many = c.plan(slice_bytes=one.kv_bytes_per_layer // 3 + (1 << 16), chunk_tokens=128)
+            assert many.n_slices == 3 and many.n_items == one.n_items
         vkv.kv_sched_set_overlap(c.pool, True)
         stream = torch.cuda.Stream()
         out = torch.empty((wl.num_seqs, g.num_q_heads, g.head_dim), dtype=torch.float32, device="cuda:0")

@@ -198,9 +198,11 @@ int kv_attn_check(vkv_pool* pool, void* workspace, void* stream);
  * paged_decode_attn_slice does on its own: its slices store their partial
  * results only, and one small launch behind the layer's last slice (enqueued
  * with it, so a yield lands before that slice or after the merge) merges every
- * split (sequence, kv head) in chunk order; the bits are the same.  Such a layer
- * must therefore be run through this call from its first slice to its last, not
- * partly through paged_decode_attn_slice. */
+ * split (sequence, kv head) in chunk order and clears the progress counters; the
+ * bits are the same.  Slices of such a layer that were enqueued on their own
+ * before this call takes over (cursor > 0) are fine; the other way round is not:
+ * a layer that this call has begun must be finished by this call, because its
+ * slices have not counted their chunks for paged_decode_attn_slice to go by. */
 int kv_attn_run_layer(vkv_pool* pool, int32_t layer, int32_t* cursor_slice,
                       const void* q_bf16, const int32_t* block_table, int32_t max_blk,
                       void* workspace, void* out_f32, float softmax_scale,

@@ -182,6 +182,13 @@ def test_yield_resume_is_bit_identical_at_every_slice(overlap):
             assert (st, cur) == (vkv.VKV_OK, info.n_slices)
             torch.cuda.synchronize()
             assert np.array_equal(out.cpu().numpy(), full), f"resume at slice {k}"
+        # the layers above began slice by slice (every chunk counted where it ran) and were finished by the
+        # scheduler, which merges a layer of this many slices behind its last slice: no count may be left
+        # over for the next layer, run slice by slice on the same workspace
+        q1, q1_t = c.q_dev(1)
+        got1 = c.attention(1, q1_t)
+        vkv.kv_attn_bind(c.pool, c.ws)               # counters zeroed
+        assert np.array_equal(c.attention(1, q1_t), got1)
     finally:
         c.close()
 
